@@ -1,0 +1,384 @@
+/*
+ * CPU oracle for the full-batch GCN hot path (MG-GCN, arXiv 2110.08688).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, fp64, written from the paper's
+ * equations; it shares no code, header, table or helper with the HIP library
+ * and must never be called from the product path.  Only tests, the smoke
+ * check and the bench's cpu_baseline leg may load it.
+ *
+ * What is the plain definition and what is a reading of the paper:
+ *   - Every function below is the textbook definition of the operation it
+ *     names (CSR product, dense product, ReLU, softmax cross-entropy, chain
+ *     rule), evaluated in double precision in index order.  Nothing here is
+ *     an approximation, so "parity unpinned" applies to none of them; the
+ *     pins are in tests/test_oracle_*.py (dense brute force, closed forms,
+ *     scipy / numpy / torch-autograd third opinions, finite differences).
+ *   - Readings of points the paper leaves open are marked "Reading:".
+ *
+ * Parallelism: OpenMP over independent output rows (or output columns for the
+ * scatter form) only, so every output element is summed in the same order as
+ * the serial loop would sum it.
+ *
+ * Conventions: dense matrices are row-major with a leading dimension (ld),
+ * indices are int32, all pointers are host pointers.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define REF_OK 0
+#define REF_E_ARG (-1)
+#define REF_E_CSR (-2)
+#define REF_E_MEM (-3)
+
+enum { REF_NORM_SYM = 0, REF_NORM_MEAN_IN = 1 };
+enum { REF_OP_N = 0, REF_OP_T = 1 };
+enum { REF_GEMM_FIRST = 0, REF_SPMM_FIRST = 1 };
+
+/* ------------------------------------------------------------------------
+ * Pattern checks
+ * --------------------------------------------------------------------- */
+
+/* rows sorted strictly ascending, indices in range */
+int mggcn_ref_csr_validate(int n_rows, int n_cols, const int32_t* rowptr, const int32_t* colidx) {
+  if (n_rows < 0 || n_cols < 0 || !rowptr) return REF_E_ARG;
+  if (rowptr[0] != 0) return REF_E_CSR;
+  for (int i = 0; i < n_rows; ++i) {
+    if (rowptr[i + 1] < rowptr[i]) return REF_E_CSR;
+    for (int32_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+      if (colidx[k] < 0 || colidx[k] >= n_cols) return REF_E_CSR;
+      if (k > rowptr[i] && colidx[k] <= colidx[k - 1]) return REF_E_CSR;
+    }
+  }
+  return REF_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * Normalised adjacency (Eq. 1-2 of the paper; Kipf-style self-loops)
+ *
+ *   A~  = pattern(A) united with the diagonal          (Reading: an existing
+ *         (i,i) stays a single entry of weight 1; rows i >= n_cols of a
+ *         rectangular block get no diagonal)
+ *   SYM : A^_ij = 1 / sqrt(d_i * d_j), d = number of entries in row i of A~
+ *         (Reading: for a non-symmetric pattern both factors are row counts;
+ *          a rectangular block passes deg_row / deg_col explicitly)
+ *   MEAN_IN (Eq. 2): A^_uv = A~_uv / sum_w A~_wv = 1 / (entries in column v)
+ *
+ * rowptr_out has n_rows+1 entries; colidx_out / val_out need room for
+ * nnz_in + min(n_rows, n_cols) entries.  Returns nnz of A~ (>= 0) or an error.
+ * --------------------------------------------------------------------- */
+int64_t mggcn_ref_csr_normalize(int n_rows, int n_cols, const int32_t* rowptr_in,
+                                const int32_t* colidx_in, int mode, const double* deg_row,
+                                const double* deg_col, int32_t* rowptr_out, int32_t* colidx_out,
+                                double* val_out) {
+  if (mggcn_ref_csr_validate(n_rows, n_cols, rowptr_in, colidx_in) != REF_OK) return REF_E_CSR;
+  if (mode != REF_NORM_SYM && mode != REF_NORM_MEAN_IN) return REF_E_ARG;
+  if (n_rows != n_cols && mode == REF_NORM_SYM && (!deg_row || !deg_col)) return REF_E_ARG;
+
+  /* 1. pattern with diagonal, columns kept ascending */
+  int64_t nnz = 0;
+  rowptr_out[0] = 0;
+  for (int i = 0; i < n_rows; ++i) {
+    int placed = (i >= n_cols); /* nothing to place outside the column range */
+    for (int32_t k = rowptr_in[i]; k < rowptr_in[i + 1]; ++k) {
+      const int32_t j = colidx_in[k];
+      if (!placed && j >= i) {
+        if (j != i) colidx_out[nnz++] = i;
+        placed = 1;
+      }
+      colidx_out[nnz++] = j;
+    }
+    if (!placed) colidx_out[nnz++] = i;
+    if (nnz > INT32_MAX) return REF_E_ARG;
+    rowptr_out[i + 1] = (int32_t)nnz;
+  }
+
+  /* 2. degrees as exact integers */
+  double* drow = (double*)malloc(sizeof(double) * (size_t)(n_rows > 0 ? n_rows : 1));
+  double* dcol = (double*)calloc((size_t)(n_cols > 0 ? n_cols : 1), sizeof(double));
+  if (!drow || !dcol) { free(drow); free(dcol); return REF_E_MEM; }
+  for (int i = 0; i < n_rows; ++i) drow[i] = (double)(rowptr_out[i + 1] - rowptr_out[i]);
+  for (int64_t k = 0; k < nnz; ++k) dcol[colidx_out[k]] += 1.0;
+
+  /* 3. values */
+  for (int i = 0; i < n_rows; ++i) {
+    for (int32_t k = rowptr_out[i]; k < rowptr_out[i + 1]; ++k) {
+      const int32_t j = colidx_out[k];
+      if (mode == REF_NORM_SYM) {
+        const double di = deg_row ? deg_row[i] : drow[i];
+        const double dj = deg_col ? deg_col[j] : drow[j]; /* square: row count of vertex j */
+        val_out[k] = 1.0 / sqrt(di * dj);
+      } else {
+        const double dj = deg_col ? deg_col[j] : dcol[j];
+        val_out[k] = 1.0 / dj;
+      }
+    }
+  }
+  free(drow);
+  free(dcol);
+  return nnz;
+}
+
+/* Explicit transpose of a CSR matrix; rows of the result have ascending columns. */
+int mggcn_ref_csr_transpose(int n_rows, int n_cols, const int32_t* rowptr, const int32_t* colidx,
+                            const double* val, int32_t* rowptr_t, int32_t* colidx_t,
+                            double* val_t) {
+  const int64_t nnz = rowptr[n_rows];
+  int32_t* cur = (int32_t*)calloc((size_t)n_cols + 1, sizeof(int32_t));
+  if (!cur) return REF_E_MEM;
+  for (int64_t k = 0; k < nnz; ++k) cur[colidx[k] + 1]++;
+  rowptr_t[0] = 0;
+  for (int j = 0; j < n_cols; ++j) rowptr_t[j + 1] = rowptr_t[j] + cur[j + 1];
+  for (int j = 0; j < n_cols; ++j) cur[j] = rowptr_t[j];
+  for (int i = 0; i < n_rows; ++i) /* ascending i => ascending columns in each result row */
+    for (int32_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+      const int32_t p = cur[colidx[k]]++;
+      colidx_t[p] = i;
+      val_t[p] = val[k];
+    }
+  free(cur);
+  return REF_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * SpMM (Eq. 6 forward, Eq. 9 backward):  Y = op(A^) * X + beta * Y
+ *   op = N :  Y[i,f] = sum_k val[k] * X[colidx[k], f]   over row i, CSR order
+ *   op = T :  Y[j,f] = sum_{(i,j)} val_ij * X[i, f]      scatter, ascending i
+ * A^ is n_rows x n_cols.  For op N, X has n_cols rows and Y n_rows rows; for
+ * op T the other way round.
+ * --------------------------------------------------------------------- */
+int mggcn_ref_spmm(int op, int n_rows, int n_cols, const int32_t* rowptr, const int32_t* colidx,
+                   const double* val, const double* X, int64_t ldx, int F, double beta, double* Y,
+                   int64_t ldy) {
+  if (F < 0 || ldx < F || ldy < F) return REF_E_ARG;
+  const int out_rows = (op == REF_OP_N) ? n_rows : n_cols;
+#pragma omp parallel for schedule(static)
+  for (int i = 0; i < out_rows; ++i)
+    for (int f = 0; f < F; ++f) Y[i * ldy + f] = (beta == 0.0) ? 0.0 : beta * Y[i * ldy + f];
+
+  if (op == REF_OP_N) {
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int i = 0; i < n_rows; ++i)
+      for (int32_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+        const double a = val[k];
+        const double* x = X + (int64_t)colidx[k] * ldx;
+        for (int f = 0; f < F; ++f) Y[i * ldy + f] += a * x[f];
+      }
+  } else {
+    /* each thread owns a band of feature columns, so the scatter is race-free
+       and every Y[j,f] is accumulated in ascending i exactly as written above */
+#pragma omp parallel
+    {
+      int nt = 1, t = 0;
+#ifdef _OPENMP
+      nt = omp_get_num_threads();
+      t = omp_get_thread_num();
+#endif
+      const int f0 = (int)((int64_t)F * t / nt), f1 = (int)((int64_t)F * (t + 1) / nt);
+      if (f1 > f0)
+        for (int i = 0; i < n_rows; ++i)
+          for (int32_t k = rowptr[i]; k < rowptr[i + 1]; ++k) {
+            const double a = val[k];
+            double* y = Y + (int64_t)colidx[k] * ldy;
+            const double* x = X + (int64_t)i * ldx;
+            for (int f = f0; f < f1; ++f) y[f] += a * x[f];
+          }
+    }
+  }
+  return REF_OK;
+}
+
+/* ------------------------------------------------------------------------
+ * GeMM (Eq. 5, 10, 11):  C = op(A) * op(B) + beta * C,  C is M x N, inner K.
+ *   opA = N: A is M x K;  opA = T: A is K x M (used as its transpose)
+ *   opB = N: B is K x N;  opB = T: B is N x K
+ * --------------------------------------------------------------------- */
+int mggcn_ref_gemm(int opA, int opB, int M, int N, int K, const double* A, int64_t lda,
+                   const double* B, int64_t ldb, double beta, double* C, int64_t ldc) {
+  if (M < 0 || N < 0 || K < 0 || ldc < N) return REF_E_ARG;
+#pragma omp parallel for schedule(static)
+  for (int m = 0; m < M; ++m) {
+    double* c = C + (int64_t)m * ldc;
+    for (int n = 0; n < N; ++n) c[n] = (beta == 0.0) ? 0.0 : beta * c[n];
+    for (int k = 0; k < K; ++k) {
+      const double a = (opA == REF_OP_N) ? A[(int64_t)m * lda + k] : A[(int64_t)k * lda + m];
+      if (opB == REF_OP_N) {
+        const double* b = B + (int64_t)k * ldb;
+        for (int n = 0; n < N; ++n) c[n] += a * b[n];
+      } else {
+        for (int n = 0; n < N; ++n) c[n] += a * B[(int64_t)n * ldb + k];
+      }
+    }
+  }
+  return REF_OK;
+}
+
+/* ReLU (Eq. 7) in place */
+void mggcn_ref_relu(int64_t rows, int cols, double* Z, int64_t ld) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int f = 0; f < cols; ++f)
+      if (!(Z[i * ld + f] > 0.0)) Z[i * ld + f] = 0.0;
+}
+
+/* ReLU' (Eq. 8): G <- G where act > 0, else 0.  Reading: derivative 0 at act <= 0;
+   act may be the pre- or the post-activation value (same mask). */
+void mggcn_ref_relu_bwd(int64_t rows, int cols, const double* act, int64_t lda, double* G,
+                        int64_t ldg) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int f = 0; f < cols; ++f)
+      if (!(act[i * lda + f] > 0.0)) G[i * ldg + f] = 0.0;
+}
+
+/* Softmax cross-entropy, mean over all n rows (Reading: every vertex is labelled,
+   no mask), and its gradient dZ = (softmax(Z) - onehot) / n.  dZ may alias Z. */
+int mggcn_ref_softmax_ce(int64_t n, int C, const double* Z, int64_t ldz, const int32_t* labels,
+                         double* loss_out, double* dZ, int64_t ldd) {
+  if (n <= 0 || C <= 0) return REF_E_ARG;
+  double total = 0.0;
+  for (int64_t i = 0; i < n; ++i) { /* serial: one fixed summation order for the mean */
+    const double* z = Z + i * ldz;
+    if (labels[i] < 0 || labels[i] >= C) return REF_E_ARG;
+    double mx = z[0];
+    for (int c = 1; c < C; ++c) if (z[c] > mx) mx = z[c];
+    double s = 0.0;
+    for (int c = 0; c < C; ++c) s += exp(z[c] - mx);
+    const double lse = mx + log(s);
+    total += lse - z[labels[i]];
+    if (dZ) {
+      for (int c = 0; c < C; ++c) {
+        const double p = exp(z[c] - lse);
+        dZ[i * ldd + c] = (p - (c == labels[i] ? 1.0 : 0.0)) / (double)n;
+      }
+    }
+  }
+  if (loss_out) *loss_out = total / (double)n;
+  return REF_OK;
+}
+
+/* Order rule ("Order of Computation"): SpMM first iff d_in < d_out; tie -> GeMM first. */
+int mggcn_ref_order(int d_in, int d_out) { return d_in < d_out ? REF_SPMM_FIRST : REF_GEMM_FIRST; }
+
+static double* dalloc(int64_t rows, int64_t cols) {
+  return (double*)calloc((size_t)(rows > 0 ? rows : 1) * (size_t)(cols > 0 ? cols : 1), sizeof(double));
+}
+
+/* ------------------------------------------------------------------------
+ * One layer forward (Eq. 5-7):  H_out = act( A^ * H_in * W )
+ *   order GEMM_FIRST:  HW = H_in*W ; Z = A^*HW
+ *   order SPMM_FIRST:  P  = A^*H_in ; Z = P*W
+ * A^ is n x n here (square graph), op N.  relu != 0 applies Eq. 7.
+ * --------------------------------------------------------------------- */
+int mggcn_ref_layer_fwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                        const double* W, int64_t ldw, double* H_out, int64_t ldo) {
+  int rc;
+  if (order == REF_GEMM_FIRST) {
+    double* HW = dalloc(n, d_out);
+    if (!HW) return REF_E_MEM;
+    rc = mggcn_ref_gemm(REF_OP_N, REF_OP_N, n, d_out, d_in, H_in, ldh, W, ldw, 0.0, HW, d_out);
+    if (!rc) rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, HW, d_out, d_out, 0.0, H_out, ldo);
+    free(HW);
+  } else {
+    double* P = dalloc(n, d_in);
+    if (!P) return REF_E_MEM;
+    rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, 0.0, P, d_in);
+    if (!rc) rc = mggcn_ref_gemm(REF_OP_N, REF_OP_N, n, d_out, d_in, P, d_in, W, ldw, 0.0, H_out, ldo);
+    free(P);
+  }
+  if (!rc && relu) mggcn_ref_relu(n, d_out, H_out, ldo);
+  return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * One layer backward (Eq. 8-11), exact chain rule for Z = A^ * H_in * W:
+ *   Z_G = G (.) 1[H_out > 0]   if the layer had a ReLU, else Z_G = G
+ *   W_G = H_in^T * (A^^T * Z_G)           (Reading of Eq. 10: shaped like W)
+ *   H_G = (A^^T * Z_G) * W^T              (Eq. 9, 11)
+ * Both operation orders give the same derivative; `order` picks which
+ * association is evaluated so that both can be checked against each other:
+ *   GEMM_FIRST:  T = A^^T Z_G ; W_G = H_in^T T ; H_G = T W^T
+ *   SPMM_FIRST:  P = A^ H_in ; W_G = P^T Z_G ; U = Z_G W^T ; H_G = A^^T U
+ * G is overwritten by Z_G.  H_G may be NULL (first layer: no input gradient).
+ * --------------------------------------------------------------------- */
+int mggcn_ref_layer_bwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                        const double* H_out, int64_t ldo, double* G, int64_t ldg, const double* W,
+                        int64_t ldw, double* W_G, int64_t ldwg, double* H_G, int64_t ldhg) {
+  int rc = REF_OK;
+  if (relu) mggcn_ref_relu_bwd(n, d_out, H_out, ldo, G, ldg);
+  if (order == REF_GEMM_FIRST) {
+    double* T = dalloc(n, d_out);
+    if (!T) return REF_E_MEM;
+    rc = mggcn_ref_spmm(REF_OP_T, n, n, rowptr, colidx, val, G, ldg, d_out, 0.0, T, d_out);
+    if (!rc) rc = mggcn_ref_gemm(REF_OP_T, REF_OP_N, d_in, d_out, n, H_in, ldh, T, d_out, 0.0, W_G, ldwg);
+    if (!rc && H_G) rc = mggcn_ref_gemm(REF_OP_N, REF_OP_T, n, d_in, d_out, T, d_out, W, ldw, 0.0, H_G, ldhg);
+    free(T);
+  } else {
+    double* P = dalloc(n, d_in);
+    if (!P) return REF_E_MEM;
+    rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, 0.0, P, d_in);
+    if (!rc) rc = mggcn_ref_gemm(REF_OP_T, REF_OP_N, d_in, d_out, n, P, d_in, G, ldg, 0.0, W_G, ldwg);
+    free(P);
+    if (!rc && H_G) {
+      double* U = dalloc(n, d_in);
+      if (!U) return REF_E_MEM;
+      rc = mggcn_ref_gemm(REF_OP_N, REF_OP_T, n, d_in, d_out, G, ldg, W, ldw, 0.0, U, d_in);
+      if (!rc) rc = mggcn_ref_spmm(REF_OP_T, n, n, rowptr, colidx, val, U, d_in, d_in, 0.0, H_G, ldhg);
+      free(U);
+    }
+  }
+  return rc;
+}
+
+/* ------------------------------------------------------------------------
+ * One epoch without optimiser: L forward layers, softmax-CE, L backward layers.
+ *   dims[0..L]  layer widths;  W[l] is dims[l] x dims[l+1], dense (ld = dims[l+1])
+ *   orders[l]   operation order per layer, or NULL for the paper's rule
+ *   Reading: no ReLU on the last layer (its output are the logits).
+ * Outputs: *loss, W_G[l] (same shapes as W[l]); logits_out (n x dims[L]) optional.
+ * --------------------------------------------------------------------- */
+int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
+                    const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
+                    const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
+                    double* logits_out) {
+  if (L < 1) return REF_E_ARG;
+  int rc = REF_OK;
+  double** H = (double**)calloc((size_t)L + 1, sizeof(double*)); /* H[l] = input of layer l */
+  if (!H) return REF_E_MEM;
+  H[0] = (double*)X;
+  for (int l = 0; l < L && !rc; ++l) {
+    H[l + 1] = dalloc(n, dims[l + 1]);
+    if (!H[l + 1]) { rc = REF_E_MEM; break; }
+    const int ord = orders ? orders[l] : mggcn_ref_order(dims[l], dims[l + 1]);
+    rc = mggcn_ref_layer_fwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, l + 1 < L,
+                             l == 0 ? X : H[l], l == 0 ? ldx : dims[l], W[l], dims[l + 1], H[l + 1],
+                             dims[l + 1]);
+  }
+  double* G = NULL;
+  if (!rc) {
+    if (logits_out) memcpy(logits_out, H[L], sizeof(double) * (size_t)n * (size_t)dims[L]);
+    G = dalloc(n, dims[L]);
+    if (!G) rc = REF_E_MEM;
+  }
+  if (!rc) rc = mggcn_ref_softmax_ce(n, dims[L], H[L], dims[L], labels, loss, G, dims[L]);
+  for (int l = L - 1; l >= 0 && !rc; --l) {
+    const int ord = orders ? orders[l] : mggcn_ref_order(dims[l], dims[l + 1]);
+    double* HG = (l > 0) ? dalloc(n, dims[l]) : NULL;
+    if (l > 0 && !HG) { rc = REF_E_MEM; break; }
+    rc = mggcn_ref_layer_bwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, l + 1 < L,
+                             l == 0 ? X : H[l], l == 0 ? ldx : dims[l], H[l + 1], dims[l + 1], G,
+                             dims[l + 1], W[l], dims[l + 1], W_G[l], dims[l + 1], HG, dims[l]);
+    free(G);
+    G = HG;
+  }
+  free(G);
+  for (int l = 1; l <= L; ++l) free(H[l]);
+  free(H);
+  return rc;
+}
