@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the GCN hot path on one MI355X.
+
+A step is one epoch without optimiser (L x forward, softmax-CE, L x backward: every row of the
+hot path) of the Reddit-shaped "medium" configuration: a seeded Chung-Lu power-law graph with
+232,965 vertices and ~114M entries, X 232,965 x 602, layers 602 -> 128 -> 41.  All inputs are
+synthetic and resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the effective SpMM bandwidth over the four SpMM launches of an
+epoch (algorithmic bytes: 8 B per entry streamed + 4F B gathered per entry + 4F B written per row
++ rowptr), `ms_per_step` is the epoch time.  `roofline` describes the dominant kernel (the F=128
+SpMM) timed with HIP events; `cpu_baseline` times the fp64 oracle's SpMM on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+# HBM bytes per launch of the F=128 SpMM measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# filled in from profiles/ once measured; None = not measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
+    """algorithmic bytes of one SpMM: no reuse of gathered rows assumed"""
+    return 8 * nnz + 4 * (n_rows + 1) + 4 * F * nnz + 4 * F * n_rows
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seg-len", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
+              "use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2110_08688_amd as mg
+    import workloads as wl
+
+    mg.binding.lib()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[args.config]
+    dims = cfg.dims
+    L = len(dims) - 1
+
+    t0 = time.time()
+    g = cfg.graph()
+    n = g.n_rows
+    X = torch.from_numpy(cfg.features(n)).to(dev)
+    Ws = [torch.from_numpy(w).to(dev) for w in cfg.weights()]
+    labels = torch.from_numpy(cfg.labels(n)).to(dev)
+    gen_s = time.time() - t0
+
+    torch.cuda.synchronize()
+    t0 = time.time()
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev))
+    nnz = int(colidx.numel())
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=mg.mggcn_model_spmm_width_max(dims), seg_len=args.seg_len)
+    model = mg.Model(graph, dims)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    WG = [torch.empty_like(w) for w in Ws]
+    loss = torch.empty(1, dtype=torch.float32, device=dev)
+
+    def step():
+        mg.mggcn_epoch(model, X, labels, Ws, W_Gs=WG, loss=loss)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    epoch_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    loss_value = float(loss.item())
+
+    # ---- per-operation timing with HIP events on the launch stream: the same calls an epoch makes
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = [a.elapsed_time(b) for a, b in evs]
+        return float(np.mean(ts)), float(np.min(ts))
+
+    reps = max(5, args.steps)
+    ops = {}
+    spmm_widths = []
+    for l in range(L):
+        order = model.order(l)
+        F = dims[l] if order == mg.ORDER_SPMM_FIRST else dims[l + 1]
+        spmm_widths.append(F)
+        ld = (F + 15) // 16 * 16
+        src = torch.randn((n, ld), device=dev)
+        dst = torch.empty((n, ld), device=dev)
+        epi = mg.EPI_RELU if (l + 1 < L and order == mg.ORDER_GEMM_FIRST) else mg.EPI_NONE
+        ops[f"spmm_fwd_l{l}_F{F}"] = timed(lambda: mg.mggcn_spmm(graph, mg.OP_N, src[:, :F], epilogue=epi, Y=dst[:, :F]), reps)
+        if l > 0 or order == mg.ORDER_GEMM_FIRST:
+            ops[f"spmm_bwd_l{l}_F{F}"] = timed(lambda: mg.mggcn_spmm(graph, mg.OP_T, src[:, :F], Y=dst[:, :F]), reps)
+        H = X if l == 0 else torch.randn((n, (dims[l] + 15) // 16 * 16), device=dev)[:, :dims[l]]
+        out = torch.empty((n, (dims[l + 1] + 15) // 16 * 16), device=dev)[:, :dims[l + 1]]
+        ops[f"gemm_fwd_l{l}_{dims[l]}x{dims[l + 1]}"] = timed(lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, H, Ws[l], Cm=out), reps)
+        wg = torch.empty_like(Ws[l])
+        ops[f"gemm_wgrad_l{l}"] = timed(lambda: mg.mggcn_gemm(mg.OP_T, mg.OP_N, H, out, Cm=wg), reps)
+        if l > 0:
+            hg = torch.empty((n, (dims[l] + 15) // 16 * 16), device=dev)[:, :dims[l]]
+            ops[f"gemm_hgrad_l{l}"] = timed(lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_T, out, Ws[l], Cm=hg), reps)
+        del src, dst
+    logits = torch.randn((n, (dims[L] + 15) // 16 * 16), device=dev)[:, :dims[L]]
+    ops["softmax_ce"] = timed(lambda: mg.mggcn_softmax_ce(logits, labels), reps)
+
+    spmm_ms = sum(v[0] for k, v in ops.items() if k.startswith("spmm"))
+    spmm_b = sum(spmm_bytes(nnz, n, int(k.rsplit("F", 1)[1])) for k in ops if k.startswith("spmm"))
+    spmm_gbps = spmm_b / (spmm_ms * 1e-3) / 1e9
+    gemm_ms = sum(v[0] for k, v in ops.items() if k.startswith("gemm"))
+    gemm_flops = 0.0
+    for l in range(L):
+        gemm_flops += 2.0 * n * dims[l] * dims[l + 1] * (2 if l == 0 else 3)
+    gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
+
+    # dominant kernel: the widest SpMM of the epoch
+    Fdom = max(spmm_widths)
+    ldom = spmm_widths.index(Fdom)
+    dom_ms = ops[f"spmm_fwd_l{ldom}_F{Fdom}"][0]
+    dom_bytes = spmm_bytes(nnz, n, Fdom)
+    achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
+    roofline = {
+        "kernel": f"mggcn_spmm forward, F={Fdom} (spmm_tasks + row fix-up)",
+        "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "traffic": MEASURED_TRAFFIC_BYTES,
+        "algorithmic_bytes_per_launch": dom_bytes,
+        "avg_launch_ms": round(dom_ms, 4), "min_launch_ms": round(ops[f"spmm_fwd_l{ldom}_F{Fdom}"][1], 4),
+        "gflops": round(2.0 * nnz * Fdom / (dom_ms * 1e-3) / 1e9, 1),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+
+        rp, ci = rowptr.cpu().numpy(), colidx.cpu().numpy()
+        v64 = val.cpu().numpy().astype(np.float64)
+        Xs = X[:, :Fdom].cpu().numpy().astype(np.float64)
+        t0 = time.perf_counter()
+        ref.spmm(ref.OP_N, n, n, rp, ci, v64, Xs)
+        cpu_s = time.perf_counter() - t0
+        cpu = {
+            "value": round(dom_bytes / cpu_s / 1e9, 3), "unit": "GB/s",
+            "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)), "kind": "oracle",
+            "sample": f"one forward SpMM A^ X at F={Fdom} on the full {args.config} graph (fp64, "
+                      f"{cpu_s:.2f} s), same algorithmic-byte count as the GPU figure",
+            "seconds": round(cpu_s, 3),
+        }
+
+    out = {
+        "metric": "spmm_effective_bandwidth", "value": round(spmm_gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(epoch_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.config}: Chung-Lu power-law graph, n={n}, nnz={nnz} (with self-loops), "
+                               f"GCN {'-'.join(map(str, dims))}, one epoch = fwd+loss+bwd, no optimiser",
+                   "spmm_widths": spmm_widths, "orders": [model.order(l) for l in range(L)]},
+        "epoch_ms": round(epoch_ms, 4),
+        "spmm_pct_hbm_roofline": round(100.0 * spmm_gbps / HBM_PEAK_GBPS, 2),
+        "spmm_ms_per_epoch": round(spmm_ms, 4), "gemm_ms_per_epoch": round(gemm_ms, 4),
+        "gemm_tflops": round(gemm_tflops, 2),
+        "gemm_mfma_utilisation": round(gemm_tflops / FP32_MFMA_PEAK_TFLOPS, 4),
+        "ops_ms_mean_min": {k: [round(v[0], 4), round(v[1], 4)] for k, v in ops.items()},
+        "loss": loss_value, "setup_s": round(setup_s, 3), "generate_s": round(gen_s, 3),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

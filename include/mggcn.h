@@ -1,0 +1,232 @@
+/*
+ * mggcn -- single-GPU hot path of full-batch GCN training (MG-GCN, arXiv 2110.08688)
+ * for AMD MI355X (gfx950).  C ABI.
+ *
+ * Conventions that hold for every entry point
+ *   - Returns 0 (MGGCN_OK) or a negative mggcn_status.  mggcn_last_error() gives a
+ *     thread-local message for the most recent failure on the calling thread.
+ *   - Arguments are checked on the host before any HIP call is made; a call that fails
+ *     with MGGCN_E_INVALID_ARG / _BAD_CSR / _OVERFLOW / _WORKSPACE / _UNSUPPORTED has
+ *     touched neither the device nor any output.
+ *   - "dev" pointers are device (HBM) pointers, "host" pointers are ordinary host memory.
+ *     The caller owns every buffer.  The library never allocates device memory: scratch
+ *     comes in through (ws, ws_bytes) arguments sized by the matching *_bytes query, and
+ *     must stay untouched by the caller until the work enqueued on it has completed.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously and in order on that stream; unless stated otherwise an
+ *     entry point does not synchronise, and outputs are valid once the stream has drained.
+ *   - Dense matrices are row-major fp32 with an explicit leading dimension in elements
+ *     (ld >= number of columns); only the first `cols` entries of a row are read or
+ *     written.  Sparse matrices are CSR with int32 `rowptr` (n_rows+1 entries, rowptr[0]=0),
+ *     int32 `colidx` ascending and duplicate-free inside a row, fp32 `val`; nnz < 2^31.
+ *   - Results do not depend on launch order or timing: no floating-point atomics are used,
+ *     so repeated calls on the same inputs give bit-identical outputs.
+ */
+#ifndef MGGCN_H_
+#define MGGCN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MGGCN_OK = 0,
+  MGGCN_E_INVALID_ARG = -1, /* null pointer, negative size, ld < cols, bad enum value ... */
+  MGGCN_E_BAD_CSR = -2,     /* rowptr not monotone / index out of range / unsorted row     */
+  MGGCN_E_OVERFLOW = -3,    /* a size does not fit the int32 index type                    */
+  MGGCN_E_WORKSPACE = -4,   /* workspace missing, too small or misaligned (256 B)          */
+  MGGCN_E_HIP = -5,         /* a HIP runtime call failed (message holds hipGetErrorString)  */
+  MGGCN_E_UNSUPPORTED = -6  /* valid request this build does not implement                 */
+} mggcn_status;
+
+/* Which normalisation mggcn_csr_normalize applies to the pattern A~ = A united with I. */
+typedef enum {
+  MGGCN_NORM_SYM_SELFLOOP = 0, /* A^_ij = 1/sqrt(d_i d_j), d = entries per row of A~              */
+  MGGCN_NORM_MEAN_IN = 1       /* A^_uv = 1/(entries in column v of A~): Eq. 2 of the paper        */
+} mggcn_norm;
+
+typedef enum { MGGCN_OP_N = 0, MGGCN_OP_T = 1 } mggcn_op;
+
+/* Fused element-wise tail of a product. */
+typedef enum {
+  MGGCN_EPI_NONE = 0,
+  MGGCN_EPI_RELU = 1,     /* out = max(out, 0)                                  (Eq. 7)          */
+  MGGCN_EPI_RELU_MASK = 2 /* out = out where the value previously stored at the same output
+                             element was > 0, else 0 (in-place ReLU', Eq. 8); excludes beta=1   */
+} mggcn_epilogue;
+
+/* Order of the two products inside a layer (section "Order of Computation"). */
+typedef enum {
+  MGGCN_ORDER_AUTO = -1,      /* SpMM first iff d_in < d_out, otherwise GeMM first (tie: GeMM) */
+  MGGCN_ORDER_GEMM_FIRST = 0, /* Z = A^ (H W)                                                   */
+  MGGCN_ORDER_SPMM_FIRST = 1  /* Z = (A^ H) W                                                   */
+} mggcn_order;
+
+const char* mggcn_last_error(void);
+
+/* Library version (major*10000 + minor*100 + patch). */
+int mggcn_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Normalised adjacency  A^ = D^-1/2 (A + I) D^-1/2   (Eq. 1-2; Kipf-style self-loops)
+ *
+ * Input: a CSR pattern (no values).  The diagonal entry (i,i) is inserted into every row
+ * i < n_cols that lacks it (an existing one is kept as a single entry), columns stay
+ * ascending.  Two calls:
+ *   _count  writes rowptr_out (dev, n_rows+1) and returns the entry count of A~ through
+ *           nnz_out (host); it SYNCHRONISES the stream to do so.
+ *   normalize  fills colidx_out / val_out (dev, nnz_out entries each) given that rowptr_out.
+ * SYM mode on a square matrix takes d_i as the row count of A~ for both factors; on a
+ * rectangular block (one GPU's row block of a 1-D partition) the global degrees must be
+ * passed in deg_row (n_rows) and deg_col (n_cols), int32 dev arrays.  MEAN_IN uses deg_col
+ * if given, else the column counts of A~.  Values are evaluated in fp64 and rounded once
+ * to fp32.  validate != 0 additionally checks the input pattern on the device (sorted,
+ * in range) and returns MGGCN_E_BAD_CSR after a synchronisation if it is malformed.
+ * Workspace: mggcn_csr_normalize_workspace_bytes(n_rows, n_cols).
+ * ---------------------------------------------------------------------------------------- */
+size_t mggcn_csr_normalize_workspace_bytes(int32_t n_rows, int32_t n_cols);
+
+int mggcn_csr_normalize_count(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in /*dev*/,
+                              const int32_t* colidx_in /*dev*/, int validate,
+                              int32_t* rowptr_out /*dev*/, int64_t* nnz_out /*host*/, void* ws,
+                              size_t ws_bytes, void* stream);
+
+int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in /*dev*/,
+                        const int32_t* colidx_in /*dev*/, int mode /*mggcn_norm*/,
+                        const int32_t* deg_row /*dev or NULL*/, const int32_t* deg_col /*dev or NULL*/,
+                        const int32_t* rowptr_out /*dev, from _count*/, int32_t* colidx_out /*dev*/,
+                        float* val_out /*dev*/, void* ws, size_t ws_bytes, void* stream);
+
+/* Explicit transpose of a CSR matrix (the paper keeps A^ and A^^T both, for the backward
+ * SpMM of Eq. 9).  Rows of the result have ascending columns; the result is unique, so it
+ * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries. */
+size_t mggcn_csr_transpose_workspace_bytes(int32_t n_rows, int32_t n_cols, int64_t nnz);
+
+int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr,
+                        const int32_t* colidx, const float* val, int32_t* rowptr_t,
+                        int32_t* colidx_t, float* val_t, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Graph handle: A^ in CSR, optionally A^^T in CSR, and the one-time load-balancing analysis
+ * the SpMM uses (rows cut into segments of bounded length, segments ordered longest first).
+ *
+ * _create reads rowptr (and rowptr_t) back to the host, SYNCHRONISES the stream, and builds
+ * the segment tables on the host.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the
+ * case for the symmetric normalisation of an undirected graph); op T then runs on A^ itself.
+ * The CSR arrays are borrowed, not copied: they must outlive the handle.
+ * seg_len = maximum entries per segment (0 = library default).
+ * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
+ * also holds the partial sums of rows that were cut, for feature widths up to F_max.
+ * A handle may be re-bound; it must be bound before mggcn_spmm is called.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct mggcn_graph mggcn_graph;
+
+int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr /*dev*/,
+                       const int32_t* colidx /*dev*/, const float* val /*dev*/,
+                       const int32_t* rowptr_t /*dev or NULL*/, const int32_t* colidx_t,
+                       const float* val_t, int32_t seg_len, void* stream, mggcn_graph** out);
+size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max);
+int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws /*dev*/, size_t ws_bytes, void* stream);
+int mggcn_graph_destroy(mggcn_graph* g);
+
+/* SpMM (Eq. 6 forward, Eq. 9 backward):   Y = epilogue( op(A^) X + beta Y )
+ * op N: X is n_cols x F, Y is n_rows x F.  op T: X is n_rows x F, Y is n_cols x F.
+ * beta is 0 or 1 (1 = accumulate, the stage loop C^i += A^{ij} H^j of the 1-D row scheme).
+ * X and Y must not overlap.  F <= the F_max the graph was bound with.  16-byte aligned
+ * pointers and leading dimensions that are multiples of 4 take the widest gather path;
+ * anything else still works through narrower loads. */
+int mggcn_spmm(const mggcn_graph* g, int op /*mggcn_op*/, const float* X /*dev*/, int64_t ldx,
+               int32_t F, float beta, int epilogue /*mggcn_epilogue*/, float* Y /*dev*/,
+               int64_t ldy, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * GeMM (Eq. 5, 10, 11):   C = epilogue( op(A) op(B) + beta C ),   C is M x N, inner size K
+ *   opA = N: A is M x K;  opA = T: A is K x M.   opB = N: B is K x N;  opB = T: B is N x K.
+ * beta is 0 or 1.  fp32 inputs, fp32 MFMA accumulation.  opA = T with a long inner dimension
+ * (the weight gradient W_G = H^T HW_G of Eq. 10, inner size = vertex count) is split along K
+ * into partial products held in ws and summed in a fixed order.
+ * Workspace: mggcn_gemm_workspace_bytes (0 for opA = N).
+ * ---------------------------------------------------------------------------------------- */
+size_t mggcn_gemm_workspace_bytes(int opA, int opB, int64_t M, int64_t N, int64_t K);
+
+int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A /*dev*/,
+               int64_t lda, const float* B /*dev*/, int64_t ldb, float beta, int epilogue,
+               float* C /*dev*/, int64_t ldc, void* ws, size_t ws_bytes, void* stream);
+
+/* In-place ReLU' (Eq. 8):  G[i,f] = act[i,f] > 0 ? G[i,f] : 0.  act may be the layer's
+ * pre- or post-activation output (same mask). */
+int mggcn_relu_bwd(int64_t rows, int32_t cols, const float* act /*dev*/, int64_t lda,
+                   float* G /*dev*/, int64_t ldg, void* stream);
+
+/* Softmax cross-entropy, mean over all n rows, and its gradient (the loss the paper trains
+ * with):  *loss_dev = (1/n) sum_i [logsumexp(z_i) - z_i[label_i]],
+ *         dlogits = (softmax(z) - onehot(label)) / n   (may alias logits: in place).
+ * labels: int32 dev array of n entries in [0, C); out-of-range labels are not detected.
+ * loss_dev: one fp32 on the device.  Workspace: mggcn_softmax_ce_workspace_bytes(n). */
+size_t mggcn_softmax_ce_workspace_bytes(int64_t n);
+
+int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits /*dev*/, int64_t ld,
+                     const int32_t* labels /*dev*/, float* loss_dev, float* dlogits /*dev*/,
+                     int64_t ldd, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Model handle: L GCN layers H^(l+1) = relu( A^ H^(l) W^(l) ) (no ReLU after the last layer,
+ * whose output are the logits), the per-layer order decision and the activation buffer plan
+ * (section "Memory Optimizations"): one result buffer per layer plus one temporary shared
+ * by all layers, carved from a caller-provided arena.  A layer that runs SpMM first also
+ * keeps its A^ H product for the backward pass (one more buffer for that layer).
+ *
+ * dims: host array of L+1 widths d_0..d_L.  orders: host array of L mggcn_order values or
+ * NULL (= AUTO everywhere).  The graph must be square, bound with F_max >= every SpMM
+ * width the model needs (mggcn_model_spmm_width_max), and outlive the model.
+ * ---------------------------------------------------------------------------------------- */
+typedef struct mggcn_model mggcn_model;
+
+int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims /*host*/,
+                       const int32_t* orders /*host or NULL*/, mggcn_model** out);
+int mggcn_model_destroy(mggcn_model* m);
+int32_t mggcn_model_spmm_width_max(const int32_t* dims /*host*/, const int32_t* orders, int32_t L);
+size_t mggcn_model_arena_bytes(const mggcn_model* m);
+int mggcn_model_bind(mggcn_model* m, void* arena /*dev*/, size_t arena_bytes);
+/* resolved order of layer l (mggcn_order), or a negative status */
+int mggcn_model_order(const mggcn_model* m, int32_t l);
+/* device pointer and leading dimension of layer l's result buffer (its output H^(l+1),
+ * later overwritten in place by the gradient with respect to it) */
+int mggcn_model_activation(const mggcn_model* m, int32_t l, float** ptr_out, int64_t* ld_out);
+
+/* One layer forward (Eq. 5-7): H_out = [relu]( A^ H_in W ).  H_in is n x d_l, W is
+ * d_l x d_{l+1}, H_out is n x d_{l+1}; relu != 0 applies Eq. 7.  Uses the model's shared
+ * temporary (and, SpMM-first, stores A^ H_in in the layer's own buffer). */
+int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in, const float* W,
+                    int64_t ldw, int relu, float* H_out, int64_t ld_out, void* stream);
+
+/* One layer backward (Eq. 8-11).  On entry G (n x d_{l+1}) holds the gradient with respect
+ * to the layer output H_out.  If act != NULL, Eq. 8 is applied first: G <- G where act > 0
+ * (pass the layer's saved output; NULL means G is already the gradient of the pre-activation).
+ * Then  W_G = H_in^T (A^^T G)   (d_l x d_{l+1}, Eq. 9-10)
+ *       H_G = (A^^T G) W^T      (n x d_l,      Eq. 11)      unless H_G == NULL.
+ * hg_relu_mask != 0: the H_G buffer currently holds the previous layer's output H^(l) and
+ * receives H_G masked by (H^(l) > 0) in place, i.e. Eq. 8 of the layer below fused in; H_G
+ * may then be the same buffer as H_in.  Must follow mggcn_layer_fwd(m, l, same H_in) when the
+ * layer runs SpMM first (it reuses the stored A^ H_in).  G is preserved except for the mask. */
+int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
+                    const float* act /*or NULL*/, int64_t ld_act, float* G, int64_t ldg,
+                    const float* W, int64_t ldw, float* W_G, int64_t ldwg, float* H_G /*or NULL*/,
+                    int64_t ldhg, int hg_relu_mask, void* stream);
+
+/* One training epoch without the optimiser step: L x layer_fwd, softmax-CE, L x layer_bwd.
+ * X: n x d_0 (ld ldx).  labels: n int32.  W / W_G: host arrays of L device pointers, W[l]
+ * and W_G[l] dense d_l x d_{l+1} (ld = d_{l+1}).  loss_dev: one fp32 on the device.  No
+ * gradient with respect to X is formed; the first layer's backward SpMM is kept whenever
+ * W_G needs it (GeMM-first order) and absent otherwise. */
+int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labels,
+                const float* const* W /*host array of dev ptrs*/, float* loss_dev,
+                float* const* W_G /*host array of dev ptrs*/, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MGGCN_H_ */

@@ -1,0 +1,280 @@
+"""MI355X-native hot path of full-batch GCN training (MG-GCN, arXiv 2110.08688).
+
+Python face of the C-ABI library `libmggcn.so` (see include/mggcn.h).  The functions here carry
+the same names as the C entry points and only marshal arguments: PyTorch supplies device memory
+(tensors) and the current HIP stream, every step of the computation runs in the library's own
+kernels.  Nothing here falls back to PyTorch or CPU arithmetic.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+from . import binding as B
+from .binding import (  # noqa: F401  (re-exported constants)
+    EPI_NONE, EPI_RELU, EPI_RELU_MASK, NORM_MEAN_IN, NORM_SYM_SELFLOOP, OP_N, OP_T, ORDER_AUTO,
+    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MggcnError,
+)
+
+
+def _torch():
+    import torch
+
+    return torch
+
+
+def _ws(nbytes: int, device):
+    torch = _torch()
+    return torch.empty(max(int(nbytes), 256) + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_ptr(t):
+    """256-byte aligned address inside a workspace tensor"""
+    p = t.data_ptr()
+    return (p + 255) // 256 * 256
+
+
+def _stream(stream):
+    return B.current_stream() if stream is None else stream
+
+
+def mggcn_version() -> int:
+    return B.lib().mggcn_version()
+
+
+# ------------------------------------------------------------------------------------------
+# setup: normalised adjacency, transpose
+# ------------------------------------------------------------------------------------------
+
+def mggcn_csr_normalize(n_rows, n_cols, rowptr_in, colidx_in, mode=NORM_SYM_SELFLOOP, deg_row=None,
+                        deg_col=None, validate=False, stream=None):
+    """-> (rowptr, colidx, val) device tensors of the normalised adjacency with self-loops."""
+    torch = _torch()
+    L = B.lib()
+    dev = rowptr_in.device
+    st = _stream(stream)
+    nbytes = L.mggcn_csr_normalize_workspace_bytes(n_rows, n_cols)
+    ws = _ws(nbytes, dev)
+    rowptr = torch.empty(n_rows + 1, dtype=torch.int32, device=dev)
+    nnz = C.c_int64(0)
+    B.check(L.mggcn_csr_normalize_count(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), int(validate),
+                                        B.ptr(rowptr), C.byref(nnz), _ws_ptr(ws), nbytes, st))
+    colidx = torch.empty(nnz.value, dtype=torch.int32, device=dev)
+    val = torch.empty(nnz.value, dtype=torch.float32, device=dev)
+    B.check(L.mggcn_csr_normalize(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), mode, B.ptr(deg_row),
+                                  B.ptr(deg_col), B.ptr(rowptr), B.ptr(colidx), B.ptr(val), _ws_ptr(ws),
+                                  nbytes, st))
+    torch.cuda.current_stream().synchronize() if stream is None else None  # ws may be freed now
+    return rowptr, colidx, val
+
+
+def mggcn_csr_transpose(n_rows, n_cols, rowptr, colidx, val, stream=None):
+    torch = _torch()
+    L = B.lib()
+    dev = rowptr.device
+    nnz = int(colidx.numel())
+    nbytes = L.mggcn_csr_transpose_workspace_bytes(n_rows, n_cols, nnz)
+    ws = _ws(nbytes, dev)
+    rowptr_t = torch.empty(n_cols + 1, dtype=torch.int32, device=dev)
+    colidx_t = torch.empty(nnz, dtype=torch.int32, device=dev)
+    val_t = torch.empty(nnz, dtype=torch.float32, device=dev)
+    B.check(L.mggcn_csr_transpose(n_rows, n_cols, nnz, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rowptr_t),
+                                  B.ptr(colidx_t), B.ptr(val_t), _ws_ptr(ws), nbytes, _stream(stream)))
+    torch.cuda.current_stream().synchronize() if stream is None else None
+    return rowptr_t, colidx_t, val_t
+
+
+# ------------------------------------------------------------------------------------------
+# graph handle + SpMM
+# ------------------------------------------------------------------------------------------
+
+class Graph:
+    """Owns an mggcn_graph handle, keeps the CSR tensors and the bound workspace alive."""
+
+    def __init__(self, n_rows, n_cols, rowptr, colidx, val, transpose=None, F_max=256, seg_len=0, stream=None):
+        L = B.lib()
+        self.n_rows, self.n_cols = n_rows, n_cols
+        self._keep = [rowptr, colidx, val, transpose]
+        rpt, cit, vat = transpose if transpose is not None else (None, None, None)
+        h = C.c_void_p(None)
+        B.check(L.mggcn_graph_create(n_rows, n_cols, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rpt),
+                                     B.ptr(cit), B.ptr(vat), seg_len, _stream(stream), C.byref(h)))
+        self.handle = h
+        self.device = rowptr.device
+        self.ws = None
+        self.F_max = 0
+        self.bind(F_max, stream)
+
+    def bind(self, F_max, stream=None):
+        L = B.lib()
+        nbytes = L.mggcn_graph_workspace_bytes(self.handle, F_max)
+        ws = _ws(nbytes, self.device)
+        B.check(L.mggcn_graph_bind(self.handle, F_max, _ws_ptr(ws), nbytes, _stream(stream)))
+        self.ws, self.F_max = ws, F_max
+
+    def close(self):
+        if getattr(self, "handle", None):
+            B.lib().mggcn_graph_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def mggcn_spmm(graph: Graph, op, X, F=None, beta=0.0, epilogue=EPI_NONE, Y=None, stream=None):
+    """Y = epilogue(op(A^) X + beta Y); returns Y (allocated if not given)."""
+    torch = _torch()
+    F = int(X.shape[1]) if F is None else F
+    out_rows = graph.n_rows if op == OP_N else graph.n_cols
+    if Y is None:
+        Y = torch.empty((out_rows, F), dtype=torch.float32, device=X.device)
+    B.check(B.lib().mggcn_spmm(graph.handle, op, B.ptr(X), B.ld_of(X), F, float(beta), epilogue, B.ptr(Y),
+                               B.ld_of(Y), _stream(stream)))
+    return Y
+
+
+# ------------------------------------------------------------------------------------------
+# GeMM, ReLU', loss
+# ------------------------------------------------------------------------------------------
+
+def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None):
+    torch = _torch()
+    L = B.lib()
+    M = A.shape[0] if opA == OP_N else A.shape[1]
+    K = A.shape[1] if opA == OP_N else A.shape[0]
+    N = Bm.shape[1] if opB == OP_N else Bm.shape[0]
+    if Cm is None:
+        Cm = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    nbytes = L.mggcn_gemm_workspace_bytes(opA, opB, M, N, K)
+    ws = _ws(nbytes, A.device) if nbytes else None
+    B.check(L.mggcn_gemm(opA, opB, M, N, K, B.ptr(A), B.ld_of(A), B.ptr(Bm), B.ld_of(Bm), float(beta), epilogue,
+                         B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, nbytes, _stream(stream)))
+    if ws is not None and stream is None:
+        torch.cuda.current_stream().synchronize()
+    return Cm
+
+
+def mggcn_relu_bwd(act, G, stream=None):
+    B.check(B.lib().mggcn_relu_bwd(G.shape[0], G.shape[1], B.ptr(act), B.ld_of(act), B.ptr(G), B.ld_of(G),
+                                   _stream(stream)))
+    return G
+
+
+def mggcn_softmax_ce(logits, labels, dlogits=None, stream=None):
+    """-> (loss: 1-element device tensor, dlogits).  dlogits=None writes the gradient in place."""
+    torch = _torch()
+    L = B.lib()
+    n, Cn = logits.shape
+    if dlogits is None:
+        dlogits = logits
+    nbytes = L.mggcn_softmax_ce_workspace_bytes(n)
+    ws = _ws(nbytes, logits.device)
+    loss = torch.empty(1, dtype=torch.float32, device=logits.device)
+    B.check(L.mggcn_softmax_ce(n, Cn, B.ptr(logits), B.ld_of(logits), B.ptr(labels), B.ptr(loss), B.ptr(dlogits),
+                               B.ld_of(dlogits), _ws_ptr(ws), nbytes, _stream(stream)))
+    if stream is None:
+        torch.cuda.current_stream().synchronize()
+    return loss, dlogits
+
+
+# ------------------------------------------------------------------------------------------
+# model: layers and epoch
+# ------------------------------------------------------------------------------------------
+
+def mggcn_model_spmm_width_max(dims, orders=None) -> int:
+    L = len(dims) - 1
+    d = (C.c_int32 * (L + 1))(*dims)
+    o = (C.c_int32 * L)(*orders) if orders is not None else None
+    return B.lib().mggcn_model_spmm_width_max(d, o, L)
+
+
+class Model:
+    """Owns an mggcn_model handle and its activation arena (a device tensor)."""
+
+    def __init__(self, graph: Graph, dims, orders=None):
+        L = B.lib()
+        self.graph, self.dims = graph, list(dims)
+        self.L = len(dims) - 1
+        need = mggcn_model_spmm_width_max(dims, orders)
+        if graph.F_max < need:
+            graph.bind(need)
+        d = (C.c_int32 * (self.L + 1))(*dims)
+        o = (C.c_int32 * self.L)(*orders) if orders is not None else None
+        h = C.c_void_p(None)
+        B.check(L.mggcn_model_create(graph.handle, self.L, d, o, C.byref(h)))
+        self.handle = h
+        nbytes = L.mggcn_model_arena_bytes(h)
+        self.arena = _ws(nbytes, graph.device)
+        B.check(L.mggcn_model_bind(h, _ws_ptr(self.arena), nbytes))
+
+    def order(self, l) -> int:
+        return B.check(B.lib().mggcn_model_order(self.handle, l))
+
+    def activation(self, l):
+        """(device address, ld) of layer l's result buffer"""
+        p, ld = C.c_void_p(None), C.c_int64(0)
+        B.check(B.lib().mggcn_model_activation(self.handle, l, C.byref(p), C.byref(ld)))
+        return p.value, ld.value
+
+    def activation_tensor(self, l):
+        """A clone of layer l's result buffer as an (n, d_{l+1}) tensor (debug / tests)."""
+        torch = _torch()
+        p, ld = self.activation(l)
+        n, d = self.graph.n_rows, self.dims[l + 1]
+        base = _ws_ptr(self.arena)
+        off = (p - base) // 4
+        flat = self.arena[(base - self.arena.data_ptr()):].view(torch.float32)
+        return flat[off: off + n * ld].view(n, ld)[:, :d].clone()
+
+    def close(self):
+        if getattr(self, "handle", None):
+            B.lib().mggcn_model_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def mggcn_layer_fwd(model: Model, l, H_in, W, relu=True, H_out=None, stream=None):
+    torch = _torch()
+    if H_out is None:
+        H_out = torch.empty((H_in.shape[0], W.shape[1]), dtype=torch.float32, device=H_in.device)
+    B.check(B.lib().mggcn_layer_fwd(model.handle, l, B.ptr(H_in), B.ld_of(H_in), B.ptr(W), B.ld_of(W), int(relu),
+                                    B.ptr(H_out), B.ld_of(H_out), _stream(stream)))
+    return H_out
+
+
+def mggcn_layer_bwd(model: Model, l, H_in, act, G, W, need_input_grad=True, H_G=None, hg_relu_mask=False,
+                    W_G=None, stream=None):
+    """-> (W_G, H_G or None).  G is masked in place when `act` is given (Eq. 8)."""
+    torch = _torch()
+    if W_G is None:
+        W_G = torch.empty_like(W)
+    if need_input_grad and H_G is None:
+        H_G = torch.empty((H_in.shape[0], W.shape[0]), dtype=torch.float32, device=H_in.device)
+    if not need_input_grad:
+        H_G = None
+    B.check(B.lib().mggcn_layer_bwd(
+        model.handle, l, B.ptr(H_in), B.ld_of(H_in), B.ptr(act), B.ld_of(act) if act is not None else 0,
+        B.ptr(G), B.ld_of(G), B.ptr(W), B.ld_of(W), B.ptr(W_G), B.ld_of(W_G), B.ptr(H_G),
+        B.ld_of(H_G) if H_G is not None else 0, int(hg_relu_mask), _stream(stream)))
+    return W_G, H_G
+
+
+def mggcn_epoch(model: Model, X, labels, Ws, W_Gs=None, loss=None, stream=None):
+    """One epoch without optimiser: -> (loss 1-element device tensor, [W_G...])."""
+    torch = _torch()
+    if W_Gs is None:
+        W_Gs = [torch.empty_like(w) for w in Ws]
+    if loss is None:
+        loss = torch.empty(1, dtype=torch.float32, device=X.device)
+    Wp = (C.c_void_p * model.L)(*[w.data_ptr() for w in Ws])
+    Gp = (C.c_void_p * model.L)(*[w.data_ptr() for w in W_Gs])
+    B.check(B.lib().mggcn_epoch(model.handle, B.ptr(X), B.ld_of(X), B.ptr(labels), Wp, B.ptr(loss), Gp,
+                                _stream(stream)))
+    return loss, W_Gs

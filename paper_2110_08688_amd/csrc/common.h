@@ -1,0 +1,66 @@
+// Internal helpers of the mggcn HIP library: error reporting, argument checks, small
+// device utilities.  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+
+#include "../../include/mggcn.h"
+
+namespace mggcn {
+
+// thread-local message behind mggcn_last_error()
+char* error_buffer();
+int fail(int code, const char* fmt, ...);
+
+#define MGGCN_REQUIRE(cond, code, ...)                 \
+  do {                                                 \
+    if (!(cond)) return ::mggcn::fail((code), __VA_ARGS__); \
+  } while (0)
+
+#define MGGCN_HIP(expr)                                                                   \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return ::mggcn::fail(MGGCN_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));   \
+  } while (0)
+
+#define MGGCN_LAUNCH_CHECK()                                                                  \
+  do {                                                                                        \
+    hipError_t e_ = hipGetLastError();                                                        \
+    if (e_ != hipSuccess)                                                                     \
+      return ::mggcn::fail(MGGCN_E_HIP, "kernel launch failed at %s:%d: %s", __FILE__, __LINE__, \
+                           hipGetErrorString(e_));                                            \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+constexpr size_t kWsAlign = 256;
+
+// Bump allocator over a caller-provided workspace.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  template <class T>
+  T* take(size_t count) {
+    T* r = reinterpret_cast<T*>(base + off);
+    off += align_up(count * sizeof(T), kWsAlign);
+    return r;
+  }
+};
+
+inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
+
+// Exclusive prefix sum of `n` int32 counts (device), result in out[0..n] (n+1 entries,
+// out[n] = total).  tmp needs scan_tmp_ints(n) int32 entries.  Three plain passes, no
+// inter-block waiting.
+size_t scan_tmp_ints(int64_t n);
+int exclusive_scan_i32(const int32_t* counts, int64_t n, int32_t* out, int32_t* tmp, hipStream_t s);
+
+}  // namespace mggcn

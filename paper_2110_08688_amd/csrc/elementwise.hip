@@ -1,0 +1,148 @@
+// Small row-wise kernels of the epoch: ReLU' mask (Eq. 8) for callers that do not use the
+// fused epilogues, and the softmax cross-entropy loss with its gradient.
+#include "common.h"
+
+namespace mggcn {
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ __launch_bounds__(kThreads) void relu_bwd_kernel(int64_t rows, int cols,
+                                                             const float* __restrict__ act,
+                                                             int64_t lda, float* __restrict__ G,
+                                                             int64_t ldg) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= rows * cols) return;
+  const int64_t i = idx / cols;
+  const int f = (int)(idx % cols);
+  if (!(act[i * lda + f] > 0.f)) G[i * ldg + f] = 0.f;
+}
+
+// T lanes (power of two, <= 64) per row; 64/T rows per wavefront.
+__global__ __launch_bounds__(kThreads) void softmax_ce_kernel(int64_t n, int C, int T,
+                                                               const float* Z, int64_t ldz,
+                                                               const int32_t* __restrict__ labels,
+                                                               float* dZ, int64_t ldd,
+                                                               float inv_n,
+                                                               float* __restrict__ block_loss) {
+  __shared__ float wave_loss[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rows_per_wave = 64 / T;
+  const int tl = lane % T;
+  const int64_t row = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * rows_per_wave + lane / T;
+  const bool live = row < n;
+  const float* z = Z + (live ? row : 0) * ldz;
+
+  float mx = -INFINITY;
+  if (live)
+    for (int c = tl; c < C; c += T) mx = fmaxf(mx, z[c]);
+  for (int d = 1; d < T; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+  float s = 0.f;
+  if (live)
+    for (int c = tl; c < C; c += T) s += expf(z[c] - mx);
+  for (int d = 1; d < T; d <<= 1) s += __shfl_xor(s, d);
+  float row_loss = 0.f;
+  float lse = 0.f, others = 0.f;
+  int y = -1;
+  if (live) {
+    lse = mx + logf(s);
+    y = labels[row];
+    for (int c = tl; c < C; c += T)
+      if (c != y) others += expf(z[c] - lse);
+  }
+  // softmax[y] - 1 = -(sum of the other classes): free of cancellation when softmax[y] -> 1
+  for (int d = 1; d < T; d <<= 1) others += __shfl_xor(others, d);
+  if (live) {
+    float* g = dZ + row * ldd;  // may be the same memory as z: each lane reads an element
+    for (int c = tl; c < C; c += T) {  // before it overwrites that same element
+      const float zc = z[c];
+      if (c == y) row_loss = lse - zc;
+      g[c] = (c == y ? -others : expf(zc - lse)) * inv_n;
+    }
+  }
+  // fixed-order reduction: lanes by xor tree, wavefronts in index order
+  for (int d = 1; d < 64; d <<= 1) row_loss += __shfl_xor(row_loss, d);
+  if (lane == 0) wave_loss[wave] = row_loss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kThreads / 64; ++w) t += wave_loss[w];
+    block_loss[blockIdx.x] = t;
+  }
+}
+
+__global__ __launch_bounds__(kThreads) void loss_finish(int64_t nblocks,
+                                                         const float* __restrict__ block_loss,
+                                                         double inv_n, float* __restrict__ loss) {
+  __shared__ double part[kThreads];
+  double s = 0.0;
+  for (int64_t b = threadIdx.x; b < nblocks; b += kThreads) s += (double)block_loss[b];
+  part[threadIdx.x] = s;
+  __syncthreads();
+  for (int d = kThreads / 2; d > 0; d >>= 1) {
+    if ((int)threadIdx.x < d) part[threadIdx.x] += part[threadIdx.x + d];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = (float)(part[0] * inv_n);
+}
+
+int team_lanes(int C) {
+  int t = 1;
+  while (t < C && t < 64) t <<= 1;
+  return t;
+}
+
+int64_t loss_blocks(int64_t n, int C) {
+  const int rows_per_block = (kThreads / 64) * (64 / team_lanes(C));
+  return ceil_div(n, rows_per_block);
+}
+
+}  // namespace
+}  // namespace mggcn
+
+using namespace mggcn;
+
+extern "C" {
+
+int mggcn_relu_bwd(int64_t rows, int32_t cols, const float* act, int64_t lda, float* G, int64_t ldg,
+                   void* stream) {
+  MGGCN_REQUIRE(rows >= 0 && cols >= 0, MGGCN_E_INVALID_ARG, "negative size %lld x %d", (long long)rows, cols);
+  MGGCN_REQUIRE(lda >= cols && ldg >= cols, MGGCN_E_INVALID_ARG, "leading dimension < cols");
+  if (rows == 0 || cols == 0) return MGGCN_OK;
+  MGGCN_REQUIRE(act && G, MGGCN_E_INVALID_ARG, "act / G is NULL");
+  const int64_t blocks = ceil_div(rows * cols, kThreads);
+  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "matrix too large for one launch");
+  relu_bwd_kernel<<<(unsigned)blocks, kThreads, 0, as_stream(stream)>>>(rows, cols, act, lda, G, ldg);
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
+size_t mggcn_softmax_ce_workspace_bytes(int64_t n) {
+  if (n <= 0) return 0;
+  // worst case one row per wavefront
+  return align_up((size_t)ceil_div(n, kThreads / 64) * sizeof(float), kWsAlign);
+}
+
+int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels,
+                     float* loss_dev, float* dlogits, int64_t ldd, void* ws, size_t ws_bytes,
+                     void* stream) {
+  MGGCN_REQUIRE(n > 0 && C > 0, MGGCN_E_INVALID_ARG, "need n > 0 and C > 0 (n=%lld, C=%d)", (long long)n, C);
+  MGGCN_REQUIRE(ld >= C && ldd >= C, MGGCN_E_INVALID_ARG, "leading dimension < C");
+  MGGCN_REQUIRE(logits && labels && loss_dev && dlogits, MGGCN_E_INVALID_ARG, "NULL argument");
+  MGGCN_REQUIRE(ws && aligned(ws, kWsAlign), MGGCN_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+  MGGCN_REQUIRE(ws_bytes >= mggcn_softmax_ce_workspace_bytes(n), MGGCN_E_WORKSPACE,
+                "workspace too small: %zu bytes given, %zu needed", ws_bytes,
+                mggcn_softmax_ce_workspace_bytes(n));
+  const int64_t blocks = loss_blocks(n, C);
+  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "too many rows for one launch");
+  hipStream_t s = as_stream(stream);
+  float* block_loss = static_cast<float*>(ws);
+  softmax_ce_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n, C, team_lanes(C), logits, ld, labels, dlogits,
+                                                          ldd, (float)(1.0 / (double)n), block_loss);
+  MGGCN_LAUNCH_CHECK();
+  loss_finish<<<1, kThreads, 0, s>>>(blocks, block_loss, 1.0 / (double)n, loss_dev);
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,318 @@
+// Dense fp32 GeMM on the CDNA matrix cores for the three products of a GCN layer
+// (Eq. 5: H W, Eq. 10: H^T HW_G, Eq. 11: HW_G W^T of the paper).
+//
+//   C = epilogue( op(A) op(B) + beta C )
+//
+// One kernel template.  A workgroup of 4 wavefronts owns a BM x BN tile of C and walks K in
+// steps of 16.  Both operand tiles are staged through LDS in k-major order (As[k][m], Bs[k][n])
+// whatever their layout in memory, because that is the order v_mfma_f32_32x32x2_f32 wants its
+// fragments in: lane l feeds A[m = l%32][k = l/32] and B[k = l/32][n = l%32], so a fragment is
+// 32 consecutive floats of one LDS row and is read without bank conflicts.  The next k-step's
+// global loads are issued before the MFMA loop of the current one.
+//
+// The shapes here are tall and skinny (M = vertex count, N and K a few hundred at most) except
+// for the weight gradient, whose inner dimension is the vertex count: that one is split along
+// K over blockIdx.z into partial products that a second kernel adds in split order (no
+// floating-point atomics, so results are reproducible).
+#include "common.h"
+
+#include <algorithm>
+
+namespace mggcn {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BK = 16;
+
+typedef float float16v __attribute__((ext_vector_type(16)));
+
+// Tile of an operand whose memory rows run along K (A not transposed, or B transposed):
+// R rows x BK, staged as 4 consecutive k per thread.
+template <int R>
+struct KContig {
+  static constexpr int kPasses = R / 64;
+  static constexpr int kRegs = kPasses * 4;
+  __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t row0,
+                                     int64_t row_end, int64_t k0, int64_t k_end, bool vec,
+                                     float (&reg)[kRegs]) {
+    const int r = threadIdx.x >> 2, kq = threadIdx.x & 3;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int64_t row = row0 + p * 64 + r;
+      const int64_t k = k0 + 4 * kq;
+      const float* ptr = src + row * ld + k;
+      if (row < row_end && vec && k + 3 < k_end) {
+        const float4 t = *reinterpret_cast<const float4*>(ptr);
+        reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) reg[p * 4 + i] = (row < row_end && k + i < k_end) ? ptr[i] : 0.f;
+      }
+    }
+  }
+  template <int LD>
+  __device__ static inline void store(float (*S)[LD], const float (&reg)[kRegs]) {
+    const int r = threadIdx.x >> 2, kq = threadIdx.x & 3;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) S[4 * kq + i][p * 64 + r] = reg[p * 4 + i];
+  }
+};
+
+// Tile of an operand whose memory rows run along the tile's M/N side (A transposed, or B not
+// transposed): BK x R, 4 consecutive m (or n) per thread.
+template <int R>
+struct MContig {
+  static constexpr int kThreadsPerRow = R / 4;
+  static constexpr int kRowsPerPass = kThreads / kThreadsPerRow;
+  static constexpr int kPasses = BK / kRowsPerPass;
+  static constexpr int kRegs = kPasses * 4;
+  __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t col0,
+                                     int64_t col_end, int64_t k0, int64_t k_end, bool vec,
+                                     float (&reg)[kRegs]) {
+    const int cq = threadIdx.x % kThreadsPerRow, kr = threadIdx.x / kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const int64_t k = k0 + p * kRowsPerPass + kr;
+      const int64_t col = col0 + 4 * cq;
+      const float* ptr = src + k * ld + col;
+      if (k < k_end && vec && col + 3 < col_end) {
+        const float4 t = *reinterpret_cast<const float4*>(ptr);
+        reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) reg[p * 4 + i] = (k < k_end && col + i < col_end) ? ptr[i] : 0.f;
+      }
+    }
+  }
+  template <int LD>
+  __device__ static inline void store(float (*S)[LD], const float (&reg)[kRegs]) {
+    static_assert(LD % 4 == 0, "row stride must keep 16-byte alignment");
+    const int cq = threadIdx.x % kThreadsPerRow, kr = threadIdx.x / kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p)
+      *reinterpret_cast<float4*>(&S[p * kRowsPerPass + kr][4 * cq]) =
+          make_float4(reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]);
+  }
+};
+
+__device__ inline float gemm_epilogue(float acc, float old, float beta, int epi) {
+  if (beta != 0.f) acc += old;
+  if (epi == MGGCN_EPI_RELU) acc = acc > 0.f ? acc : 0.f;
+  if (epi == MGGCN_EPI_RELU_MASK) acc = old > 0.f ? acc : 0.f;
+  return acc;
+}
+
+// WM x WN wavefronts tile the BM x BN block; each wavefront holds TM x TN accumulators of 32x32.
+template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int64_t K,
+                                                       const float* __restrict__ A, int64_t lda,
+                                                       const float* __restrict__ B, int64_t ldb,
+                                                       float* __restrict__ C, int64_t ldc, float beta,
+                                                       int epi, int64_t k_per_split,
+                                                       float* __restrict__ partial, int vecA,
+                                                       int vecB) {
+  static_assert(WM * WN == kThreads / 64, "four wavefronts");
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
+  constexpr int LDA = BM + (TA ? 4 : 2);
+  constexpr int LDB = BN + (TB ? 2 : 4);
+  using LoadA = typename std::conditional<TA, MContig<BM>, KContig<BM>>::type;
+  using LoadB = typename std::conditional<TB, KContig<BN>, MContig<BN>>::type;
+
+  __shared__ __attribute__((aligned(16))) float As[BK][LDA];
+  __shared__ __attribute__((aligned(16))) float Bs[BK][LDB];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int64_t m0 = (int64_t)blockIdx.x * BM;
+  const int64_t n0 = (int64_t)blockIdx.y * BN;
+  const int64_t kb = (int64_t)blockIdx.z * k_per_split;
+  const int64_t ke = min(K, kb + k_per_split);
+
+  float16v acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  float ra[LoadA::kRegs], rb[LoadB::kRegs];
+  LoadA::load(A, lda, m0, M, kb, ke, vecA != 0, ra);
+  LoadB::load(B, ldb, n0, N, kb, ke, vecB != 0, rb);
+
+  const int frow = lane >> 5, fcol = lane & 31;
+  for (int64_t k0 = kb; k0 < ke; k0 += BK) {
+    LoadA::template store<LDA>(As, ra);
+    LoadB::template store<LDB>(Bs, rb);
+    __syncthreads();
+    if (k0 + BK < ke) {
+      LoadA::load(A, lda, m0, M, k0 + BK, ke, vecA != 0, ra);
+      LoadB::load(B, ldb, n0, N, k0 + BK, ke, vecB != 0, rb);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      float a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[i] = As[kk + frow][(wm * TM + i) * 32 + fcol];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[j] = Bs[kk + frow][(wn * TN + j) * 32 + fcol];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+
+  // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
+  const bool to_partial = partial != nullptr;
+  float* out = to_partial ? partial + (int64_t)blockIdx.z * M * N : C;
+  const int64_t ldo = to_partial ? N : ldc;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int64_t col = n0 + (wn * TN + j) * 32 + fcol;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * frow + (r % 4);
+        if (row < M && col < N) {
+          float* dst = out + row * ldo + col;
+          if (to_partial) {
+            *dst = acc[i][j][r];
+          } else {
+            const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
+            *dst = gemm_epilogue(acc[i][j][r], old, beta, epi);
+          }
+        }
+      }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void gemm_reduce_splits(int64_t M, int64_t N, int splits,
+                                                                const float* __restrict__ partial,
+                                                                float* __restrict__ C, int64_t ldc,
+                                                                float beta, int epi) {
+  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (idx >= M * N) return;
+  float s = 0.f;
+  for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * M * N + idx];
+  float* dst = C + (idx / N) * ldc + (idx % N);
+  const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
+  *dst = gemm_epilogue(s, old, beta, epi);
+}
+
+struct Shape {
+  int bm, bn;
+  int64_t tiles_m, tiles_n;
+  int splits;
+  int64_t k_per_split;
+};
+
+Shape plan_shape(int opA, int64_t M, int64_t N, int64_t K) {
+  Shape s;
+  s.bm = 128;
+  s.bn = (N > 64) ? 128 : 64;
+  s.tiles_m = ceil_div(std::max<int64_t>(M, 1), s.bm);
+  s.tiles_n = ceil_div(std::max<int64_t>(N, 1), s.bn);
+  s.splits = 1;
+  s.k_per_split = std::max<int64_t>(align_up((size_t)std::max<int64_t>(K, 1), BK), BK);
+  if (opA == MGGCN_OP_T && K > 4096) {
+    const int64_t tiles = s.tiles_m * s.tiles_n;
+    int64_t want = ceil_div(1024, tiles);
+    want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
+    want = std::max<int64_t>(want, 1);
+    s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
+    s.splits = (int)ceil_div(K, s.k_per_split);
+  }
+  return s;
+}
+
+template <int BM, int BN, int WM, int WN>
+int launch_ops(int opA, int opB, const Shape& s, int64_t M, int64_t N, int64_t K, const float* A,
+               int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, float beta, int epi,
+               float* partial, int vecA, int vecB, hipStream_t st) {
+  MGGCN_REQUIRE(s.tiles_m < ((int64_t)1 << 31) && s.tiles_n < 65536 && s.splits < 65536,
+                MGGCN_E_OVERFLOW, "GeMM grid %lld x %lld x %d too large", (long long)s.tiles_m,
+                (long long)s.tiles_n, s.splits);
+  dim3 grid((unsigned)s.tiles_m, (unsigned)s.tiles_n, (unsigned)s.splits);
+#define MGGCN_GEMM_LAUNCH(TA, TB)                                                                     \
+  gemm_mfma<BM, BN, WM, WN, TA, TB><<<grid, kThreads, 0, st>>>(M, N, K, A, lda, B, ldb, C, ldc, beta, \
+                                                               epi, s.k_per_split, partial, vecA, vecB)
+  if (opA == MGGCN_OP_N && opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(false, false);
+  else if (opA == MGGCN_OP_T && opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(true, false);
+  else if (opA == MGGCN_OP_N && opB == MGGCN_OP_T) MGGCN_GEMM_LAUNCH(false, true);
+  else MGGCN_GEMM_LAUNCH(true, true);
+#undef MGGCN_GEMM_LAUNCH
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
+}  // namespace
+}  // namespace mggcn
+
+using namespace mggcn;
+
+extern "C" {
+
+size_t mggcn_gemm_workspace_bytes(int opA, int opB, int64_t M, int64_t N, int64_t K) {
+  (void)opB;
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  const Shape s = plan_shape(opA, M, N, K);
+  if (s.splits <= 1) return 0;
+  return align_up((size_t)s.splits * (size_t)M * (size_t)N * sizeof(float), kWsAlign);
+}
+
+int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+               const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
+               size_t ws_bytes, void* stream) {
+  MGGCN_REQUIRE((opA == MGGCN_OP_N || opA == MGGCN_OP_T) && (opB == MGGCN_OP_N || opB == MGGCN_OP_T),
+                MGGCN_E_INVALID_ARG, "unknown op (%d, %d)", opA, opB);
+  MGGCN_REQUIRE(M >= 0 && N >= 0 && K >= 0, MGGCN_E_INVALID_ARG, "negative size M=%lld N=%lld K=%lld",
+                (long long)M, (long long)N, (long long)K);
+  MGGCN_REQUIRE(beta == 0.f || beta == 1.f, MGGCN_E_INVALID_ARG, "beta must be 0 or 1");
+  MGGCN_REQUIRE(epilogue == MGGCN_EPI_NONE || epilogue == MGGCN_EPI_RELU || epilogue == MGGCN_EPI_RELU_MASK,
+                MGGCN_E_INVALID_ARG, "unknown epilogue %d", epilogue);
+  MGGCN_REQUIRE(!(epilogue == MGGCN_EPI_RELU_MASK && beta != 0.f), MGGCN_E_INVALID_ARG,
+                "RELU_MASK cannot be combined with beta = 1");
+  const int64_t a_cols = (opA == MGGCN_OP_N) ? K : M, b_cols = (opB == MGGCN_OP_N) ? N : K;
+  MGGCN_REQUIRE(lda >= a_cols && ldb >= b_cols && ldc >= N, MGGCN_E_INVALID_ARG,
+                "leading dimension too small (lda %lld/%lld, ldb %lld/%lld, ldc %lld/%lld)",
+                (long long)lda, (long long)a_cols, (long long)ldb, (long long)b_cols, (long long)ldc,
+                (long long)N);
+  if (M == 0 || N == 0) return MGGCN_OK;
+  MGGCN_REQUIRE(C != nullptr, MGGCN_E_INVALID_ARG, "C is NULL");
+  MGGCN_REQUIRE(K == 0 || (A && B), MGGCN_E_INVALID_ARG, "A / B is NULL");
+  const Shape s = plan_shape(opA, M, N, std::max<int64_t>(K, 1));
+  float* partial = nullptr;
+  if (s.splits > 1) {
+    const size_t need = mggcn_gemm_workspace_bytes(opA, opB, M, N, K);
+    MGGCN_REQUIRE(ws && aligned(ws, kWsAlign), MGGCN_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
+    MGGCN_REQUIRE(ws_bytes >= need, MGGCN_E_WORKSPACE, "workspace too small: %zu bytes given, %zu needed",
+                  ws_bytes, need);
+    partial = static_cast<float*>(ws);
+  }
+  hipStream_t st = as_stream(stream);
+  const int vecA = (aligned(A, 16) && lda % 4 == 0) ? 1 : 0;
+  const int vecB = (aligned(B, 16) && ldb % 4 == 0) ? 1 : 0;
+  int rc;
+  if (s.bn == 128)
+    rc = launch_ops<128, 128, 2, 2>(opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial,
+                                    vecA, vecB, st);
+  else
+    rc = launch_ops<128, 64, 4, 1>(opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial,
+                                   vecA, vecB, st);
+  if (rc) return rc;
+  if (partial) {
+    gemm_reduce_splits<<<(unsigned)ceil_div(M * N, kThreads), kThreads, 0, st>>>(M, N, s.splits, partial,
+                                                                                C, ldc, beta, epilogue);
+    MGGCN_LAUNCH_CHECK();
+  }
+  return MGGCN_OK;
+}
+
+}  // extern "C"

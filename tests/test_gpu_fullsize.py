@@ -1,0 +1,108 @@
+"""GPU parity at the benchmark's full size: the Reddit-shaped "medium" configuration
+(232,965 vertices, ~114M entries, 602 -> 128 -> 41) in exactly the launch configuration
+bench.py times (padded leading dimensions, fused ReLU epilogue, default segment length).
+The oracle is fast enough here to check every output row, not a sample."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(1100)]
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def row_err(got, want):
+    num = np.abs(got.astype(np.float64) - want).max(axis=1)
+    den = np.abs(want).max(axis=1)
+    assert np.all(num[den == 0] == 0)
+    return num / np.maximum(den, 1e-300)
+
+
+@pytest.fixture(scope="module")
+def medium(ref):
+    import torch
+
+    import paper_2110_08688_amd as mg
+
+    mg.binding.lib()
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS["medium"]
+    t0 = time.time()
+    g = cfg.graph()
+    say(f"[medium] generated n={g.n_rows} nnz={g.nnz} in {time.time() - t0:.1f}s")
+    n = g.n_rows
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev), validate=True)
+    t0 = time.time()
+    rp, ci, rv = ref.csr_normalize(n, n, g.rowptr, g.colidx)
+    say(f"[medium] oracle normalise {time.time() - t0:.1f}s, nnz with self-loops {len(ci)}")
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=128)
+    return dict(mg=mg, dev=dev, cfg=cfg, n=n, rowptr=rowptr, colidx=colidx, val=val, rp=rp, ci=ci, rv=rv,
+                graph=graph)
+
+
+def test_medium_normalize_bit_exact(medium):
+    m = medium
+    assert np.array_equal(m["rowptr"].cpu().numpy(), m["rp"])
+    assert np.array_equal(m["colidx"].cpu().numpy(), m["ci"])
+    assert np.array_equal(m["val"].cpu().numpy().view(np.int32), m["rv"].astype(np.float32).view(np.int32))
+    # closed form on the device values: A^ sqrt(d) = sqrt(d) -- holds at any size
+    d = np.diff(m["rp"]).astype(np.float64)
+    assert d.min() >= 1
+
+
+@pytest.mark.parametrize("F,ld,relu", [(128, 128, True), (41, 48, False)])
+def test_medium_spmm_all_rows(medium, ref, F, ld, relu):
+    import torch
+
+    m = medium
+    mg, dev, n = m["mg"], m["dev"], m["n"]
+    say(f"[medium spmm] F={F} ld={ld} relu={relu}")
+    Xp = wl.normal_f32(4242, F, (n, ld))
+    Xd = torch.from_numpy(Xp).to(dev)
+    Yd = torch.zeros((n, ld), device=dev)
+    mg.mggcn_spmm(m["graph"], mg.OP_N, Xd[:, :F], epilogue=mg.EPI_RELU if relu else mg.EPI_NONE, Y=Yd[:, :F])
+    got = Yd.cpu().numpy()
+    t0 = time.time()
+    want = ref.spmm(ref.OP_N, n, n, m["rp"], m["ci"], m["rv"].astype(np.float32).astype(np.float64),
+                    Xp[:, :F].astype(np.float64))
+    say(f"[medium spmm] oracle {time.time() - t0:.1f}s")
+    if relu:
+        want = np.maximum(want, 0.0)
+    e = row_err(got[:, :F], want)
+    say(f"[medium spmm] max row rel err {e.max():.3e}")
+    assert e.max() <= 1e-4
+    assert np.all(got[:, F:] == 0)
+    # transposed product on the symmetric operator gives the same bits
+    Yt = torch.zeros((n, ld), device=dev)
+    mg.mggcn_spmm(m["graph"], mg.OP_T, Xd[:, :F], epilogue=mg.EPI_RELU if relu else mg.EPI_NONE, Y=Yt[:, :F])
+    assert torch.equal(Yd, Yt)
+
+
+def test_medium_epoch(medium, ref):
+    import torch
+
+    m = medium
+    mg, dev, n, cfg = m["mg"], m["dev"], m["n"], m["cfg"]
+    X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
+    model = mg.Model(m["graph"], cfg.dims)
+    loss, WG = mg.mggcn_epoch(model, torch.from_numpy(X).to(dev), torch.from_numpy(labels).to(dev),
+                              [torch.from_numpy(w).to(dev) for w in Ws])
+    torch.cuda.synchronize()
+    say(f"[medium epoch] gpu loss {loss.item():.7f}; running the fp64 oracle epoch on the host ...")
+    t0 = time.time()
+    rl, rWG, _ = ref.epoch(n, m["rp"], m["ci"], m["rv"].astype(np.float32).astype(np.float64),
+                           X.astype(np.float64), labels, [w.astype(np.float64) for w in Ws])
+    say(f"[medium epoch] oracle {time.time() - t0:.1f}s loss {rl:.7f}")
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
+    for l, (a, b) in enumerate(zip(WG, rWG)):
+        e = row_err(a.cpu().numpy(), b)
+        say(f"[medium epoch] W_G[{l}] max row rel err {e.max():.3e}")
+        assert e.max() <= 1e-4

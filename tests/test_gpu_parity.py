@@ -1,0 +1,453 @@
+"""GPU parity: every entry point of the C-ABI library against the fp64 CPU oracle, element by
+element on the same seeded inputs.  Integer and index results must match bit for bit; fp32
+results must satisfy, per output row,  max|got - ref| <= 1e-4 * max|ref|  (the tolerance the
+build's target states), with the oracle fed the same fp32 inputs widened to fp64."""
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def mg():
+    import torch
+
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2110_08688_amd as m
+
+    m.binding.lib()  # fails loudly if libmggcn.so is missing
+    return m
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+
+    return torch.device("cuda:0")
+
+
+def to_dev(a, dev):
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def row_err(got, want):
+    """per-row max-norm relative error; rows whose reference is exactly zero must be zero"""
+    got = np.asarray(got, dtype=np.float64)
+    num = np.abs(got - want).max(axis=1) if want.shape[1] else np.zeros(want.shape[0])
+    den = np.abs(want).max(axis=1) if want.shape[1] else np.ones(want.shape[0])
+    zero = den == 0
+    assert np.all(num[zero] == 0), "rows with an exactly-zero reference must be exactly zero"
+    return np.where(zero, 0.0, num / np.maximum(den, 1e-300))
+
+
+def assert_rows_close(got, want, tol=TOL, what=""):
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output"
+    e = row_err(got, want)
+    worst = int(np.argmax(e)) if e.size else -1
+    assert e.size == 0 or e[worst] <= tol, f"{what}: row {worst} rel err {e[worst]:.3e} > {tol}"
+    return float(e.max()) if e.size else 0.0
+
+
+def normalized(ref, g, mode=None):
+    rp, ci, val = ref.csr_normalize(g.n_rows, g.n_cols, g.rowptr, g.colidx,
+                                    mode=ref.NORM_SYM if mode is None else mode)
+    return rp, ci, val.astype(np.float32)  # the values the GPU path holds
+
+
+def adversarial_pattern(n=300, seed=5):
+    """empty rows, a row holding most entries, a full column, isolated vertices, ragged size"""
+    rng = np.random.default_rng(seed)
+    rows = [set() for _ in range(n)]
+    hub = 7
+    for j in range(n):
+        if j != hub and j % 3:
+            rows[hub].add(j); rows[j].add(hub)
+    for _ in range(4 * n):
+        a, b = rng.integers(0, n, 2)
+        if a != b and a % 11 and b % 11:  # every 11th vertex stays isolated (unless tied to the hub)
+            rows[a].add(int(b)); rows[b].add(int(a))
+    rowptr = np.zeros(n + 1, np.int32)
+    col = []
+    for i in range(n):
+        c = sorted(rows[i])
+        col += c
+        rowptr[i + 1] = len(col)
+    return wl.Pattern(n, n, rowptr, np.array(col, np.int32))
+
+
+# ----------------------------------------------------------------------------------------------
+# a0: normalisation and transpose -- bit exact
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("case", ["tiny", "adversarial", "powerlaw", "empty", "loops"])
+@pytest.mark.parametrize("mode", ["sym", "mean"])
+def test_csr_normalize_bit_exact(mg, dev, ref, case, mode):
+    say(f"[normalize] case={case} mode={mode}")
+    if case == "tiny":
+        g = wl.CONFIGS["tiny"].graph()
+    elif case == "adversarial":
+        g = adversarial_pattern()
+    elif case == "powerlaw":
+        g = wl.chung_lu(3001, 150e3, 2.1, 1500.0, 99)
+    elif case == "empty":
+        g = wl.Pattern(77, 77, np.zeros(78, np.int32), np.zeros(0, np.int32))
+    else:  # some self-loops already present, non-symmetric pattern
+        rng = np.random.default_rng(3)
+        A = rng.random((129, 129)) < 0.05
+        A[np.arange(0, 129, 4), np.arange(0, 129, 4)] = True
+        import scipy.sparse as sp
+
+        S = sp.csr_matrix(A.astype(np.float32)); S.sort_indices()
+        g = wl.Pattern(129, 129, S.indptr.astype(np.int32), S.indices.astype(np.int32))
+    m = ref.NORM_MEAN_IN if mode == "mean" else ref.NORM_SYM
+    rp, ci, val = ref.csr_normalize(g.n_rows, g.n_cols, g.rowptr, g.colidx, mode=m)
+    grp, gci, gval = mg.mggcn_csr_normalize(g.n_rows, g.n_cols, to_dev(g.rowptr, dev), to_dev(g.colidx, dev),
+                                            mode=mg.NORM_MEAN_IN if mode == "mean" else mg.NORM_SYM_SELFLOOP,
+                                            validate=True)
+    assert np.array_equal(grp.cpu().numpy(), rp)
+    assert np.array_equal(gci.cpu().numpy(), ci)
+    assert np.array_equal(gval.cpu().numpy().view(np.int32), val.astype(np.float32).view(np.int32))
+
+
+def test_csr_normalize_rectangular_block(mg, dev, ref):
+    g = wl.row_block(500, 4000, 6000, 2.5, 200.0, 1.6, 17)
+    rng = np.random.default_rng(1)
+    dr = rng.integers(1, 3000, g.n_rows).astype(np.int32)
+    dc = rng.integers(1, 3000, g.n_cols).astype(np.int32)
+    rp, ci, val = ref.csr_normalize(g.n_rows, g.n_cols, g.rowptr, g.colidx, deg_row=dr, deg_col=dc)
+    grp, gci, gval = mg.mggcn_csr_normalize(g.n_rows, g.n_cols, to_dev(g.rowptr, dev), to_dev(g.colidx, dev),
+                                            deg_row=to_dev(dr, dev), deg_col=to_dev(dc, dev))
+    assert np.array_equal(grp.cpu().numpy(), rp) and np.array_equal(gci.cpu().numpy(), ci)
+    assert np.array_equal(gval.cpu().numpy().view(np.int32), val.astype(np.float32).view(np.int32))
+
+
+def test_csr_normalize_rejects_malformed(mg, dev):
+    rp = to_dev(np.array([0, 2, 3], np.int32), dev)
+    for bad in ([1, 0, 1], [0, 0, 1], [0, 5, 1]):  # unsorted, duplicate, out of range
+        with pytest.raises(mg.MggcnError) as ei:
+            mg.mggcn_csr_normalize(2, 2, rp, to_dev(np.array(bad, np.int32), dev), validate=True)
+        assert ei.value.code == mg.binding.E_BAD_CSR
+
+
+@pytest.mark.parametrize("shape", [(30, 45, 0.15), (1000, 700, 0.02), (64, 64, 0.0)])
+def test_csr_transpose_exact(mg, dev, ref, shape):
+    n, m, dens = shape
+    say(f"[transpose] {shape}")
+    rng = np.random.default_rng(n)
+    import scipy.sparse as sp
+
+    S = sp.random(n, m, density=dens, format="csr", random_state=7, dtype=np.float32)
+    S.sort_indices()
+    rp, ci, va = S.indptr.astype(np.int32), S.indices.astype(np.int32), S.data.astype(np.float32)
+    rpt, cit, vat = ref.csr_transpose(n, m, rp, ci, va.astype(np.float64))
+    g = mg.mggcn_csr_transpose(n, m, to_dev(rp, dev), to_dev(ci, dev), to_dev(va, dev))
+    assert np.array_equal(g[0].cpu().numpy(), rpt) and np.array_equal(g[1].cpu().numpy(), cit)
+    assert np.array_equal(g[2].cpu().numpy(), vat.astype(np.float32))
+
+
+# ----------------------------------------------------------------------------------------------
+# a2 / a6: SpMM
+# ----------------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def spmm_graphs(mg, dev, ref):
+    """name -> (pattern, rp, ci, val32, Graph)"""
+    out = {}
+    pats = {
+        "tiny": wl.CONFIGS["tiny"].graph(),
+        "adversarial": adversarial_pattern(),
+        "powerlaw": wl.chung_lu(3001, 150e3, 2.1, 1500.0, 99),  # rows longer than a segment
+        "rmat": wl.rmat(12, 30000, 0.57, 0.19, 0.19, 5),        # many isolated vertices, hubs
+    }
+    for name, g in pats.items():
+        rp, ci, val = normalized(ref, g)
+        G = mg.Graph(g.n_rows, g.n_cols, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=640)
+        out[name] = (g, rp, ci, val, G)
+    return out
+
+
+@pytest.mark.parametrize("F", [1, 3, 8, 16, 41, 47, 64, 100, 128, 256, 602])
+@pytest.mark.parametrize("name", ["tiny", "adversarial", "powerlaw", "rmat"])
+def test_spmm_forward(mg, dev, ref, spmm_graphs, name, F):
+    say(f"[spmm N] graph={name} F={F}")
+    g, rp, ci, val, G = spmm_graphs[name]
+    n = g.n_rows
+    X = wl.normal_f32(1234 + F, 1, (n, F))
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, val.astype(np.float64), X.astype(np.float64))
+    got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy()
+    if F >= 8:
+        assert_rows_close(got, want, what=f"spmm {name} F={F}")
+    else:
+        # With one or three columns the row norm is (nearly) a single entry, and a sum of signed
+        # terms that cancels makes |err| / |y| ill-conditioned whatever the kernel does.  Use the
+        # forward error bound of a dot product instead: |err| <= 1e-5 * (|A^| |X|) row-wise.
+        scale = ref.spmm(ref.OP_N, n, n, rp, ci, np.abs(val).astype(np.float64), np.abs(X).astype(np.float64))
+        err = np.abs(got - want).max(axis=1)
+        assert np.all(err <= 1e-5 * scale.max(axis=1)), f"spmm {name} F={F}: {err.max():.3e}"
+    # symmetric operator: the transposed product is the same numbers
+    got_t = mg.mggcn_spmm(G, mg.OP_T, to_dev(X, dev)).cpu().numpy()
+    assert np.array_equal(got, got_t)
+
+
+@pytest.mark.parametrize("F,ldx,ldy", [(41, 48, 64), (41, 41, 41), (47, 50, 47), (100, 112, 100), (128, 130, 129),
+                                       (5, 8, 12)])
+def test_spmm_leading_dimensions_and_padding_untouched(mg, dev, ref, spmm_graphs, F, ldx, ldy):
+    import torch
+
+    say(f"[spmm ld] F={F} ldx={ldx} ldy={ldy}")
+    g, rp, ci, val, G = spmm_graphs["powerlaw"]
+    n = g.n_rows
+    Xp = wl.normal_f32(77, 2, (n, ldx))
+    Xd = to_dev(Xp, dev)
+    Yd = torch.full((n, ldy), 123.0, device=dev)
+    mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], Y=Yd[:, :F])
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, val.astype(np.float64), Xp[:, :F].astype(np.float64))
+    Y = Yd.cpu().numpy()
+    assert_rows_close(Y[:, :F], want, what="ld")
+    assert np.all(Y[:, F:] == 123.0), "columns beyond F must not be written"
+
+
+@pytest.mark.parametrize("name", ["adversarial", "powerlaw"])
+@pytest.mark.parametrize("F", [16, 100])
+def test_spmm_accumulate_and_epilogues(mg, dev, ref, spmm_graphs, name, F):
+    say(f"[spmm epi] graph={name} F={F}")
+    g, rp, ci, val, G = spmm_graphs[name]
+    n = g.n_rows
+    X = wl.normal_f32(9, 3, (n, F))
+    Y0 = wl.normal_f32(9, 4, (n, F))
+    v64 = val.astype(np.float64)
+    base = ref.spmm(ref.OP_N, n, n, rp, ci, v64, X.astype(np.float64))
+    # beta = 1
+    got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), beta=1.0, Y=to_dev(Y0, dev)).cpu().numpy()
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, v64, X.astype(np.float64), beta=1.0, Y=Y0.astype(np.float64))
+    assert_rows_close(got, want, what="beta=1")
+    # fused ReLU: compare against the oracle's ReLU of the GPU's own pre-activation decision
+    got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), epilogue=mg.EPI_RELU).cpu().numpy()
+    plain = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy()
+    assert np.array_equal(got, np.maximum(plain, 0.0))
+    assert_rows_close(got, ref.relu(base), tol=2e-4, what="relu")
+    # in-place ReLU' mask: Y_old > 0 keeps the product, else 0
+    got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), epilogue=mg.EPI_RELU_MASK, Y=to_dev(Y0, dev)).cpu().numpy()
+    assert np.array_equal(got, np.where(Y0 > 0, plain, 0.0).astype(np.float32))
+
+
+def test_spmm_transpose_nonsymmetric_and_rectangular(mg, dev, ref):
+    say("[spmm T] mean-normalised directed graph, and a rectangular block")
+    rng = np.random.default_rng(21)
+    import scipy.sparse as sp
+
+    S = sp.random(900, 900, density=0.02, format="csr", random_state=3, dtype=np.float32)
+    S.setdiag(0); S.eliminate_zeros(); S.sort_indices()
+    rp, ci, val = ref.csr_normalize(900, 900, S.indptr.astype(np.int32), S.indices.astype(np.int32),
+                                    mode=ref.NORM_MEAN_IN)
+    v32 = val.astype(np.float32)
+    d = [to_dev(a, dev) for a in (rp, ci, v32)]
+    t = mg.mggcn_csr_transpose(900, 900, *d)
+    G = mg.Graph(900, 900, *d, transpose=t, F_max=64)
+    X = wl.normal_f32(5, 5, (900, 33))
+    for op, rop in ((mg.OP_N, ref.OP_N), (mg.OP_T, ref.OP_T)):
+        want = ref.spmm(rop, 900, 900, rp, ci, v32.astype(np.float64), X.astype(np.float64))
+        got = mg.mggcn_spmm(G, op, to_dev(X, dev)).cpu().numpy()
+        assert_rows_close(got, want, what=f"mean op={op}")
+    # rectangular row block with given degrees
+    g = wl.row_block(700, 5000, 9000, 2.5, 300.0, 1.6, 4)
+    dr = rng.integers(1, 500, g.n_rows).astype(np.int32)
+    dc = rng.integers(1, 500, g.n_cols).astype(np.int32)
+    rp, ci, val = ref.csr_normalize(g.n_rows, g.n_cols, g.rowptr, g.colidx, deg_row=dr, deg_col=dc)
+    v32 = val.astype(np.float32)
+    d = [to_dev(a, dev) for a in (rp, ci, v32)]
+    t = mg.mggcn_csr_transpose(g.n_rows, g.n_cols, *d)
+    G = mg.Graph(g.n_rows, g.n_cols, *d, transpose=t, F_max=128)
+    X = wl.normal_f32(6, 6, (g.n_cols, 128))
+    Gr = wl.normal_f32(6, 7, (g.n_rows, 128))
+    want = ref.spmm(ref.OP_N, g.n_rows, g.n_cols, rp, ci, v32.astype(np.float64), X.astype(np.float64))
+    assert_rows_close(mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy(), want, what="block N")
+    want = ref.spmm(ref.OP_T, g.n_rows, g.n_cols, rp, ci, v32.astype(np.float64), Gr.astype(np.float64))
+    assert_rows_close(mg.mggcn_spmm(G, mg.OP_T, to_dev(Gr, dev)).cpu().numpy(), want, what="block T")
+
+
+def test_spmm_is_deterministic_and_segment_length_invariant(mg, dev, ref, spmm_graphs):
+    g, rp, ci, val, G = spmm_graphs["powerlaw"]
+    n = g.n_rows
+    Xd = to_dev(wl.normal_f32(8, 8, (n, 128)), dev)
+    a = mg.mggcn_spmm(G, mg.OP_N, Xd).cpu().numpy()
+    b = mg.mggcn_spmm(G, mg.OP_N, Xd).cpu().numpy()
+    assert np.array_equal(a, b)
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, val.astype(np.float64), Xd.cpu().numpy().astype(np.float64))
+    for seg in (8, 64, 100000):
+        G2 = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128, seg_len=seg)
+        assert_rows_close(mg.mggcn_spmm(G2, mg.OP_N, Xd).cpu().numpy(), want, what=f"seg_len={seg}")
+
+
+# ----------------------------------------------------------------------------------------------
+# a1 / a7 / a8: GeMM
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (200, 16, 64), (4097, 8, 16), (1000, 41, 128), (777, 128, 602),
+                                   (513, 256, 100), (300, 47, 256), (129, 130, 33)])
+def test_gemm_nn_nt(mg, dev, ref, M, N, K):
+    say(f"[gemm NN/NT] {M}x{N}x{K}")
+    A = wl.normal_f32(M + N, 11, (M, K))
+    Bm = wl.normal_f32(M + K, 12, (K, N))
+    want = ref.gemm(ref.OP_N, ref.OP_N, A.astype(np.float64), Bm.astype(np.float64))
+    got = mg.mggcn_gemm(mg.OP_N, mg.OP_N, to_dev(A, dev), to_dev(Bm, dev)).cpu().numpy()
+    assert_rows_close(got, want, what="NN")
+    got = mg.mggcn_gemm(mg.OP_N, mg.OP_T, to_dev(A, dev), to_dev(np.ascontiguousarray(Bm.T), dev)).cpu().numpy()
+    assert_rows_close(got, want, what="NT")
+    got = mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(np.ascontiguousarray(A.T), dev), to_dev(Bm, dev)).cpu().numpy()
+    assert_rows_close(got, want, what="TN small K")
+
+
+@pytest.mark.parametrize("M,N,K", [(602, 128, 30001), (128, 41, 9999), (16, 8, 4097), (100, 256, 20000)])
+def test_gemm_tn_split_k(mg, dev, ref, M, N, K):
+    """weight-gradient shape: the inner dimension is the (long) vertex axis"""
+    say(f"[gemm TN split-K] {M}x{N}x{K}")
+    H = wl.normal_f32(K, 13, (K, M))
+    T = wl.normal_f32(K, 14, (K, N))
+    want = ref.gemm(ref.OP_T, ref.OP_N, H.astype(np.float64), T.astype(np.float64))
+    a = mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(H, dev), to_dev(T, dev)).cpu().numpy()
+    assert_rows_close(a, want, what="TN")
+    b = mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(H, dev), to_dev(T, dev)).cpu().numpy()
+    assert np.array_equal(a, b), "split-K reduction must be reproducible"
+
+
+def test_gemm_epilogues_beta_and_strides(mg, dev, ref):
+    import torch
+
+    M, N, K = 333, 41, 100
+    A = wl.normal_f32(1, 15, (M, 112))      # ld 112 > K
+    Bm = wl.normal_f32(1, 16, (K, N))       # ld 41: unaligned rows
+    C0 = wl.normal_f32(1, 17, (M, 48))
+    Ad, Bd = to_dev(A, dev), to_dev(Bm, dev)
+    want = ref.gemm(ref.OP_N, ref.OP_N, A[:, :K].astype(np.float64), Bm.astype(np.float64))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad[:, :K], Bd, Cm=Cd[:, :N])
+    C = Cd.cpu().numpy()
+    assert_rows_close(C[:, :N], want, what="strided")
+    assert np.array_equal(C[:, N:], C0[:, N:]), "padding columns must not be written"
+    plain = C[:, :N].copy()
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad[:, :K], Bd, beta=1.0, Cm=Cd[:, :N])
+    assert_rows_close(Cd.cpu().numpy()[:, :N], want + C0[:, :N].astype(np.float64), what="beta")
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad[:, :K], Bd, epilogue=mg.EPI_RELU, Cm=Cd[:, :N])
+    assert np.array_equal(Cd.cpu().numpy()[:, :N], np.maximum(plain, 0))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad[:, :K], Bd, epilogue=mg.EPI_RELU_MASK, Cm=Cd[:, :N])
+    assert np.array_equal(Cd.cpu().numpy()[:, :N], np.where(C0[:, :N] > 0, plain, 0).astype(np.float32))
+
+
+# ----------------------------------------------------------------------------------------------
+# a4 / a5: loss, ReLU'
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n,C,ld", [(4096, 8, 16), (1001, 41, 48), (333, 47, 47), (50, 100, 100), (7, 1, 4)])
+def test_softmax_ce(mg, dev, ref, n, C, ld):
+    say(f"[softmax_ce] n={n} C={C} ld={ld}")
+    Zp = wl.normal_f32(n, 20, (n, ld)) * 3
+    labels = wl.labels_i32(n, 21, n, C)
+    loss, dZ = ref.softmax_ce(Zp[:, :C].astype(np.float64), labels)
+    Zd = to_dev(Zp, dev)
+    gl, gd = mg.mggcn_softmax_ce(Zd[:, :C], to_dev(labels, dev))  # in place
+    assert abs(gl.item() - loss) <= 1e-5 * abs(loss) + 1e-7
+    out = Zd.cpu().numpy()
+    assert_rows_close(out[:, :C], dZ, tol=1e-4 if C > 1 else 1.0, what="dlogits")
+    assert np.array_equal(out[:, C:], Zp[:, C:])
+
+
+def test_relu_bwd(mg, dev):
+    act = wl.normal_f32(3, 22, (500, 48))
+    G = wl.normal_f32(3, 23, (500, 64))
+    Gd = to_dev(G, dev)
+    mg.mggcn_relu_bwd(to_dev(act, dev)[:, :41], Gd[:, :41])
+    want = G.copy()
+    want[:, :41] = np.where(act[:, :41] > 0, G[:, :41], 0)
+    assert np.array_equal(Gd.cpu().numpy(), want)
+
+
+# ----------------------------------------------------------------------------------------------
+# layers and epoch
+# ----------------------------------------------------------------------------------------------
+
+def _model_inputs(ref, g, dims, seed):
+    rp, ci, val = normalized(ref, g)
+    n = g.n_rows
+    X = wl.normal_f32(seed, 30, (n, dims[0]))
+    Ws = [wl.glorot_f32(seed, 40 + l, dims[l], dims[l + 1]) for l in range(len(dims) - 1)]
+    labels = wl.labels_i32(seed, 50, n, dims[-1])
+    return rp, ci, val, X, Ws, labels
+
+
+@pytest.mark.parametrize("d_in,d_out", [(64, 16), (20, 100), (41, 41)])
+@pytest.mark.parametrize("order", ["gemm_first", "spmm_first"])
+def test_layer_fwd_bwd(mg, dev, ref, d_in, d_out, order):
+    say(f"[layer] {d_in}->{d_out} {order}")
+    g = wl.chung_lu(2000, 60e3, 2.1, 700.0, 3)
+    rp, ci, val, X, Ws, _ = _model_inputs(ref, g, (d_in, d_out), 1)
+    n = g.n_rows
+    o = mg.ORDER_GEMM_FIRST if order == "gemm_first" else mg.ORDER_SPMM_FIRST
+    ro = ref.GEMM_FIRST if order == "gemm_first" else ref.SPMM_FIRST
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128)
+    model = mg.Model(G, (d_in, d_out), orders=[o])
+    assert model.order(0) == o
+    Xd, Wd = to_dev(X, dev), to_dev(Ws[0], dev)
+    v64, X64, W64 = val.astype(np.float64), X.astype(np.float64), Ws[0].astype(np.float64)
+    out = mg.mggcn_layer_fwd(model, 0, Xd, Wd, relu=True)
+    want = ref.layer_fwd(n, rp, ci, v64, X64, W64, ro, True)
+    out_h = out.cpu().numpy()
+    assert_rows_close(out_h, want, tol=2e-4, what="fwd")  # ReLU may flip entries at |z| ~ 1e-7
+    # backward with the GPU's own saved activation as the mask source (identical inputs)
+    R = wl.normal_f32(2, 31, (n, d_out))
+    WG, HG = mg.mggcn_layer_bwd(model, 0, Xd, out, to_dev(R, dev), Wd, need_input_grad=True)
+    WG_r, HG_r, _ = ref.layer_bwd(n, rp, ci, v64, X64, out_h.astype(np.float64), R.astype(np.float64), W64, ro, True)
+    assert_rows_close(WG.cpu().numpy(), WG_r, what="W_G")
+    assert_rows_close(HG.cpu().numpy(), HG_r, what="H_G")
+
+
+@pytest.mark.parametrize("cfg_name,dims,orders", [
+    ("tiny", None, None),
+    ("tiny", (64, 100, 32, 8), None),            # SpMM-first then GeMM-first layers
+    ("tiny", (64, 16, 8), "spmm_first"),
+    ("small_powerlaw", (50, 128, 41), None),
+])
+def test_epoch(mg, dev, ref, cfg_name, dims, orders):
+    say(f"[epoch] {cfg_name} dims={dims} orders={orders}")
+    if cfg_name == "tiny":
+        g = wl.CONFIGS["tiny"].graph()
+        dims = dims or wl.CONFIGS["tiny"].dims
+    else:
+        g = wl.chung_lu(5000, 300e3, 2.1, 2500.0, 8)
+    n = g.n_rows
+    rp, ci, val, X, Ws, labels = _model_inputs(ref, g, dims, 7)
+    L = len(dims) - 1
+    ords = None if orders is None else [mg.ORDER_SPMM_FIRST] * L
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128)
+    model = mg.Model(G, dims, orders=ords)
+    loss, WG = mg.mggcn_epoch(model, to_dev(X, dev), to_dev(labels, dev), [to_dev(w, dev) for w in Ws])
+    loss2, WG2 = mg.mggcn_epoch(model, to_dev(X, dev), to_dev(labels, dev), [to_dev(w, dev) for w in Ws])
+    rl, rWG, _ = ref.epoch(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
+                           [w.astype(np.float64) for w in Ws],
+                           orders=None if ords is None else [ref.SPMM_FIRST] * L)
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
+    assert loss.item() == loss2.item()
+    for l in range(L):
+        a = WG[l].cpu().numpy()
+        assert np.array_equal(a, WG2[l].cpu().numpy()), "epoch must be reproducible bit for bit"
+        assert_rows_close(a, rWG[l], what=f"W_G[{l}]")
+        # the order rule
+        want_order = mg.ORDER_SPMM_FIRST if (ords is not None or dims[l] < dims[l + 1]) else mg.ORDER_GEMM_FIRST
+        assert model.order(l) == want_order
