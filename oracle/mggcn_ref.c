@@ -235,6 +235,17 @@ void mggcn_ref_relu_bwd(int64_t rows, int cols, const double* act, int64_t lda, 
       if (!(act[i * lda + f] > 0.0)) G[i * ldg + f] = 0.0;
 }
 
+/* ReLU' with the 0/1 decisions handed in (dense rows x cols bytes) instead of being taken
+   from fp64 activations.  Used for epoch-level parity: whether an activation that is zero to
+   within rounding counts as "on" is a discrete decision, and a comparison is only meaningful
+   when both sides take it from the same numbers (here: the fp32 activations of the device). */
+void mggcn_ref_apply_mask(int64_t rows, int cols, const uint8_t* mask, double* G, int64_t ldg) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int f = 0; f < cols; ++f)
+      if (!mask[i * cols + f]) G[i * ldg + f] = 0.0;
+}
+
 /* Softmax cross-entropy, mean over all n rows (Reading: every vertex is labelled,
    no mask), and its gradient dZ = (softmax(Z) - onehot) / n.  dZ may alias Z. */
 int mggcn_ref_softmax_ce(int64_t n, int C, const double* Z, int64_t ldz, const int32_t* labels,
@@ -341,12 +352,15 @@ int mggcn_ref_layer_bwd(int n, const int32_t* rowptr, const int32_t* colidx, con
  *   dims[0..L]  layer widths;  W[l] is dims[l] x dims[l+1], dense (ld = dims[l+1])
  *   orders[l]   operation order per layer, or NULL for the paper's rule
  *   Reading: no ReLU on the last layer (its output are the logits).
+ *   relu_masks  NULL, or L-1 dense byte matrices (n x dims[l+1]) with the ReLU' decisions of
+ *               the hidden layers to use in the backward pass instead of the oracle's own
+ *               (see mggcn_ref_apply_mask); the forward pass always uses Eq. 7 as is.
  * Outputs: *loss, W_G[l] (same shapes as W[l]); logits_out (n x dims[L]) optional.
  * --------------------------------------------------------------------- */
 int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
                     const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
                     const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
-                    double* logits_out) {
+                    double* logits_out, const uint8_t* const* relu_masks) {
   if (L < 1) return REF_E_ARG;
   int rc = REF_OK;
   double** H = (double**)calloc((size_t)L + 1, sizeof(double*)); /* H[l] = input of layer l */
@@ -371,7 +385,12 @@ int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const d
     const int ord = orders ? orders[l] : mggcn_ref_order(dims[l], dims[l + 1]);
     double* HG = (l > 0) ? dalloc(n, dims[l]) : NULL;
     if (l > 0 && !HG) { rc = REF_E_MEM; break; }
-    rc = mggcn_ref_layer_bwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, l + 1 < L,
+    int own_relu = l + 1 < L;
+    if (own_relu && relu_masks) {
+      mggcn_ref_apply_mask(n, dims[l + 1], relu_masks[l], G, dims[l + 1]);
+      own_relu = 0;
+    }
+    rc = mggcn_ref_layer_bwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, own_relu,
                              l == 0 ? X : H[l], l == 0 ? ldx : dims[l], H[l + 1], dims[l + 1], G,
                              dims[l + 1], W[l], dims[l + 1], W_G[l], dims[l + 1], HG, dims[l]);
     free(G);

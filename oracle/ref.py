@@ -62,7 +62,7 @@ def _load():
             i32, vp, vp, vp, i32, i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, i64, vp, i64, vp, i64,
         ]
         lib.mggcn_ref_epoch.restype = i32
-        lib.mggcn_ref_epoch.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp]
+        lib.mggcn_ref_epoch.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -230,8 +230,9 @@ def layer_bwd(n, rowptr, colidx, val, H_in, H_out, G, W, order_, relu_, need_inp
     return W_G, H_G, G
 
 
-def epoch(n, rowptr, colidx, val, X, labels, Ws, orders=None, want_logits=False):
-    """-> (loss, [W_G...], logits or None)"""
+def epoch(n, rowptr, colidx, val, X, labels, Ws, orders=None, want_logits=False, relu_masks=None):
+    """-> (loss, [W_G...], logits or None).  relu_masks: optional list of L-1 (n, d_{l+1}) 0/1 byte
+    arrays with the hidden layers' ReLU' decisions to use in the backward pass."""
     rowptr, colidx, val, X, labels = _i32(rowptr), _i32(colidx), _f64(val), _f64(X), _i32(labels)
     Ws = [_f64(w) for w in Ws]
     L = len(Ws)
@@ -244,11 +245,18 @@ def epoch(n, rowptr, colidx, val, X, labels, Ws, orders=None, want_logits=False)
     ords = None if orders is None else _i32(orders)
     logits = np.zeros((n, int(dims[-1])), dtype=np.float64) if want_logits else None
     loss = C.c_double(0.0)
+    Mp = None
+    if relu_masks is not None:
+        assert len(relu_masks) == L - 1
+        relu_masks = [np.ascontiguousarray(m, dtype=np.uint8) for m in relu_masks]
+        for l, m in enumerate(relu_masks):
+            assert m.shape == (n, int(dims[l + 1]))
+        Mp = (C.c_void_p * max(L - 1, 1))(*[m.ctypes.data for m in relu_masks])
     _check(
         _load().mggcn_ref_epoch(
             n, rowptr.ctypes.data, colidx.ctypes.data, val.ctypes.data, L, dims.ctypes.data,
             None if ords is None else ords.ctypes.data, X.ctypes.data, _ld(X), labels.ctypes.data,
-            Wp, C.byref(loss), WGp, None if logits is None else logits.ctypes.data,
+            Wp, C.byref(loss), WGp, None if logits is None else logits.ctypes.data, Mp,
         ),
         "epoch",
     )

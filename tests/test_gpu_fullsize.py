@@ -93,14 +93,25 @@ def test_medium_epoch(medium, ref):
     mg, dev, n, cfg = m["mg"], m["dev"], m["n"], m["cfg"]
     X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
     model = mg.Model(m["graph"], cfg.dims)
-    loss, WG = mg.mggcn_epoch(model, torch.from_numpy(X).to(dev), torch.from_numpy(labels).to(dev),
-                              [torch.from_numpy(w).to(dev) for w in Ws])
+    Xd, Wd = torch.from_numpy(X).to(dev), [torch.from_numpy(w).to(dev) for w in Ws]
+    loss, WG = mg.mggcn_epoch(model, Xd, torch.from_numpy(labels).to(dev), Wd)
     torch.cuda.synchronize()
     say(f"[medium epoch] gpu loss {loss.item():.7f}; running the fp64 oracle epoch on the host ...")
+    # the device's own ReLU' decisions (same forward call, same bits as inside the epoch): a
+    # hidden activation that is zero to within rounding is "on" or "off" by a coin toss, and one
+    # such entry moves a whole column of W_G[0] by ~1/sqrt(n) of its size
+    out = torch.empty((n, 128), device=dev)
+    mg.mggcn_layer_fwd(model, 0, Xd, Wd[0], relu=True, H_out=out)
+    mask = (out > 0).cpu().numpy().astype(np.uint8)
+    v64 = m["rv"].astype(np.float32).astype(np.float64)
     t0 = time.time()
-    rl, rWG, _ = ref.epoch(n, m["rp"], m["ci"], m["rv"].astype(np.float32).astype(np.float64),
-                           X.astype(np.float64), labels, [w.astype(np.float64) for w in Ws])
+    rl, rWG, _ = ref.epoch(n, m["rp"], m["ci"], v64, X.astype(np.float64), labels,
+                           [w.astype(np.float64) for w in Ws], relu_masks=[mask])
     say(f"[medium epoch] oracle {time.time() - t0:.1f}s loss {rl:.7f}")
+    own = ref.layer_fwd(n, m["rp"], m["ci"], v64, X.astype(np.float64), Ws[0].astype(np.float64),
+                        ref.GEMM_FIRST, True) > 0
+    say(f"[medium epoch] ReLU' decisions that differ between fp32 device and fp64 oracle: "
+        f"{int(np.count_nonzero(own != mask.astype(bool)))} of {mask.size}")
     assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
     for l, (a, b) in enumerate(zip(WG, rWG)):
         e = row_err(a.cpu().numpy(), b)

@@ -383,6 +383,21 @@ def test_relu_bwd(mg, dev):
 # layers and epoch
 # ----------------------------------------------------------------------------------------------
 
+def gpu_relu_decisions(mg, model, Xd, Wd):
+    """ReLU' decisions (activation > 0) of the hidden layers as the device takes them: the same
+    forward calls, hence the same bits, as inside mggcn_epoch."""
+    import torch
+
+    masks, H = [], Xd
+    for l in range(model.L - 1):
+        d = model.dims[l + 1]
+        out = torch.empty((H.shape[0], (d + 15) // 16 * 16), device=H.device)[:, :d]
+        mg.mggcn_layer_fwd(model, l, H, Wd[l], relu=True, H_out=out)
+        masks.append((out > 0).cpu().numpy().astype(np.uint8))
+        H = out
+    return masks
+
+
 def _model_inputs(ref, g, dims, seed):
     rp, ci, val = normalized(ref, g)
     n = g.n_rows
@@ -437,11 +452,16 @@ def test_epoch(mg, dev, ref, cfg_name, dims, orders):
     ords = None if orders is None else [mg.ORDER_SPMM_FIRST] * L
     G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128)
     model = mg.Model(G, dims, orders=ords)
-    loss, WG = mg.mggcn_epoch(model, to_dev(X, dev), to_dev(labels, dev), [to_dev(w, dev) for w in Ws])
-    loss2, WG2 = mg.mggcn_epoch(model, to_dev(X, dev), to_dev(labels, dev), [to_dev(w, dev) for w in Ws])
+    Xd, Wd = to_dev(X, dev), [to_dev(w, dev) for w in Ws]
+    loss, WG = mg.mggcn_epoch(model, Xd, to_dev(labels, dev), Wd)
+    loss2, WG2 = mg.mggcn_epoch(model, Xd, to_dev(labels, dev), Wd)
+    # Whether a hidden activation that is zero to within rounding counts as "on" is a discrete
+    # decision: the oracle's backward pass takes the device's fp32 decisions (one flipped entry
+    # would otherwise move a whole column of a weight gradient by far more than rounding).
+    masks = gpu_relu_decisions(mg, model, Xd, Wd)
     rl, rWG, _ = ref.epoch(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
                            [w.astype(np.float64) for w in Ws],
-                           orders=None if ords is None else [ref.SPMM_FIRST] * L)
+                           orders=None if ords is None else [ref.SPMM_FIRST] * L, relu_masks=masks)
     assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
     assert loss.item() == loss2.item()
     for l in range(L):

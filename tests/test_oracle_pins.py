@@ -469,3 +469,24 @@ def test_tiny_config_epoch_against_torch(ref):
     assert abs(loss - loss_t) < 1e-12
     for a, b in zip(WG, WG_t):
         np.testing.assert_allclose(a, b, rtol=1e-9, atol=1e-14)
+
+
+def test_epoch_with_injected_relu_decisions(ref):
+    """Handing the oracle its own ReLU' decisions changes nothing; flipping one decision at
+    (u, b) of the hidden layer changes exactly the gradient paths through unit b."""
+    n, dims = 30, (6, 9, 4)
+    rp, ci, val, X, Ws, labels = _setup_model(ref, n, dims, 123)
+    loss, WG, _ = ref.epoch(n, rp, ci, val, X, labels, Ws)
+    H1 = ref.layer_fwd(n, rp, ci, val, X, Ws[0], ref.order(6, 9), True)
+    own = (H1 > 0).astype(np.uint8)
+    loss2, WG2, _ = ref.epoch(n, rp, ci, val, X, labels, Ws, relu_masks=[own])
+    assert loss == loss2
+    for a, b in zip(WG, WG2):
+        assert np.array_equal(a, b)
+    flipped = own.copy()
+    u, b = 5, 2
+    flipped[u, b] ^= 1
+    _, WG3, _ = ref.epoch(n, rp, ci, val, X, labels, Ws, relu_masks=[flipped])
+    assert np.array_equal(WG3[1], WG[1])                 # last layer's gradient does not see the mask
+    changed = np.any(WG3[0] != WG[0], axis=0)
+    assert changed[b] and not np.any(np.delete(changed, b))
