@@ -118,6 +118,9 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * case for the symmetric normalisation of an undirected graph); op T then runs on A^ itself.
  * The CSR arrays are borrowed, not copied: they must outlive the handle.
  * seg_len = maximum entries per segment (0 = library default).
+ * n_panels = number of column panels the SpMM walks one after the other so that all wavefronts
+ * in flight gather from the same slice of X (0 = chosen from the matrix size and average row
+ * length, and then used only for operands too large for the caches; 1 = never; > 1 = always).
  * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
  * also holds the partial sums of rows that were cut, for feature widths up to F_max.
  * A handle may be re-bound; it must be bound before mggcn_spmm is called.
@@ -127,10 +130,14 @@ typedef struct mggcn_graph mggcn_graph;
 int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr /*dev*/,
                        const int32_t* colidx /*dev*/, const float* val /*dev*/,
                        const int32_t* rowptr_t /*dev or NULL*/, const int32_t* colidx_t,
-                       const float* val_t, int32_t seg_len, void* stream, mggcn_graph** out);
+                       const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
+                       mggcn_graph** out);
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max);
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws /*dev*/, size_t ws_bytes, void* stream);
 int mggcn_graph_destroy(mggcn_graph* g);
+/* Number of column-panel passes a plain (epilogue NONE or RELU) SpMM of width F with the given
+ * op makes on this graph (1 = single pass), or a negative status. */
+int mggcn_graph_panels(const mggcn_graph* g, int op /*mggcn_op*/, int32_t F);
 
 /* SpMM (Eq. 6 forward, Eq. 9 backward):   Y = epilogue( op(A^) X + beta Y )
  * op N: X is n_cols x F, Y is n_rows x F.  op T: X is n_rows x F, Y is n_cols x F.

@@ -90,14 +90,15 @@ def mggcn_csr_transpose(n_rows, n_cols, rowptr, colidx, val, stream=None):
 class Graph:
     """Owns an mggcn_graph handle, keeps the CSR tensors and the bound workspace alive."""
 
-    def __init__(self, n_rows, n_cols, rowptr, colidx, val, transpose=None, F_max=256, seg_len=0, stream=None):
+    def __init__(self, n_rows, n_cols, rowptr, colidx, val, transpose=None, F_max=256, seg_len=0, n_panels=0,
+                 stream=None):
         L = B.lib()
         self.n_rows, self.n_cols = n_rows, n_cols
         self._keep = [rowptr, colidx, val, transpose]
         rpt, cit, vat = transpose if transpose is not None else (None, None, None)
         h = C.c_void_p(None)
         B.check(L.mggcn_graph_create(n_rows, n_cols, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rpt),
-                                     B.ptr(cit), B.ptr(vat), seg_len, _stream(stream), C.byref(h)))
+                                     B.ptr(cit), B.ptr(vat), seg_len, n_panels, _stream(stream), C.byref(h)))
         self.handle = h
         self.device = rowptr.device
         self.ws = None
@@ -110,6 +111,9 @@ class Graph:
         ws = _ws(nbytes, self.device)
         B.check(L.mggcn_graph_bind(self.handle, F_max, _ws_ptr(ws), nbytes, _stream(stream)))
         self.ws, self.F_max = ws, F_max
+
+    def panels(self, F, op=OP_N) -> int:
+        return B.check(B.lib().mggcn_graph_panels(self.handle, op, F))
 
     def close(self):
         if getattr(self, "handle", None):

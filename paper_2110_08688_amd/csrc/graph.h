@@ -2,19 +2,44 @@
 // the operator is not symmetric) plus the row-segment tables the SpMM kernels walk.
 #pragma once
 
+#include <array>
 #include <cstdint>
 #include <vector>
 
 namespace mggcn {
 
+// One unit of SpMM work: `len` consecutive entries of one row, starting at entry k0.
+// len_flags packs the length with two flags:
+//   first: no earlier launch has written this row, so the caller's beta applies (else beta = 1)
+//   last : no later launch adds to this row, so the epilogue is applied here
 struct Task {
-  int32_t row, k0, k1, slot;  // slot < 0: final result of the row; else index into partials
+  int32_t row, k0;
+  uint32_t len_flags;
+  int32_t slot;  // < 0: result goes to Y; else index into the partial-sum table
 };
+constexpr uint32_t kTaskFirst = 1u << 30, kTaskLast = 1u << 29, kTaskLenMask = (1u << 29) - 1;
+
+// A (row, panel) range that was cut into several tasks: its partial sums are added in order.
 struct FixRow {
-  int32_t row, slot0, nslots, pad;
+  int32_t row, slot0, nslots;
+  uint32_t flags;  // kTaskFirst / kTaskLast as above
 };
 
-constexpr int kLenClasses = 7;  // thresholds 8*2^i, i = 0..6
+constexpr int kLenClasses = 7;  // length thresholds 8 << i, i = 0..6
+
+// Tasks of one operator, grouped by column panel (panel p holds the entries whose column lies
+// in the p-th equal slice of the column range).  One panel = the classic row split.
+struct TaskSet {
+  int32_t n_panels = 0;  // 0: not built
+  std::vector<Task> tasks;          // panel-major; inside a panel longest first
+  std::vector<int64_t> task_begin;  // n_panels + 1 offsets into tasks
+  std::vector<FixRow> fix;
+  std::vector<int64_t> fix_begin;   // n_panels + 1 offsets into fix
+  std::vector<std::array<int64_t, kLenClasses>> cnt_ge;  // per panel: tasks of length >= 8 << i
+  int64_t n_slots = 0;              // partial-sum rows needed by the widest panel
+  Task* d_tasks = nullptr;
+  FixRow* d_fix = nullptr;
+};
 
 struct Orientation {
   int32_t n_rows = 0, n_cols = 0;
@@ -22,12 +47,8 @@ struct Orientation {
   const int32_t* rowptr = nullptr;
   const int32_t* colidx = nullptr;
   const float* val = nullptr;
-  std::vector<Task> tasks;
-  std::vector<FixRow> fix;
-  int64_t n_slots = 0;
-  int64_t cnt_ge[kLenClasses] = {0};  // tasks with length >= 8 << i
-  Task* d_tasks = nullptr;
-  FixRow* d_fix = nullptr;
+  TaskSet flat;      // one panel
+  TaskSet panelled;  // several column panels (absent when the analysis decides against it)
 };
 
 }  // namespace mggcn
@@ -40,6 +61,6 @@ struct mggcn_graph {
   int64_t ldp = 0;
   float* d_partial = nullptr;
   bool bound = false;
-  int32_t chunk_lanes = 0;  // forced lanes per feature chunk (0 = widest)
+  int32_t chunk_lanes = 0;     // forced lanes per feature chunk (0 = widest)
+  int64_t panel_min_bytes = 0;  // gathered operand smaller than this: panels are not used
 };
-

@@ -7,6 +7,15 @@
 //   cut row go to a partial-sum table and a second small kernel adds them in segment order, so
 //   the result never depends on timing (no floating-point atomics).
 //
+// Column panels (the "blocking effect" the paper observes for column tiles, and the same algebra
+// as its stage loop C += A^{ij} H^j): on a dense-ish graph the gathered operand X is far larger
+// than the 8 x 4 MB of L2, and throughput follows how much of it the caches hold.  The column
+// range is therefore cut into P equal panels; columns being sorted inside a row, the entries of
+// a (row, panel) pair are a contiguous sub-range, so no data moves.  Panels run as successive
+// launches on the stream, each adding into Y (beta = 1 after a row's first panel, epilogue at its
+// last): all wavefronts in flight then gather from the same 1/P of X.  The price is one
+// read-modify-write of Y per panel, so P is capped by the average row length.
+//
 // Kernel mapping (wave64):
 //   the feature dimension runs along lanes: LPR lanes x VW floats cover one feature chunk of a
 //   dense row, so a gathered row is read with 16-byte loads that are contiguous across lanes.
@@ -31,46 +40,101 @@ namespace mggcn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kDefaultSegLen = 512;
+constexpr int kDefaultSegLen = 2048;
 
-void analyse(Orientation* o, const std::vector<int32_t>& rowptr, int32_t seg_len) {
-  const int32_t n = o->n_rows;
-  std::vector<Task> row_order;
-  row_order.reserve((size_t)n + (size_t)(o->nnz / seg_len) + 16);
-  o->fix.clear();
-  int64_t slots = 0;
-  for (int32_t i = 0; i < n; ++i) {
-    const int32_t b = rowptr[i], len = rowptr[i + 1] - b;
-    if (len <= seg_len) {
-      row_order.push_back({i, b, b + len, -1});
-    } else {
-      const int32_t nseg = (int32_t)ceil_div(len, seg_len);
-      const int32_t piece = (int32_t)ceil_div(len, nseg);
-      o->fix.push_back({i, (int32_t)slots, nseg, 0});
-      for (int32_t s = 0; s < nseg; ++s) {
-        const int32_t k0 = b + s * piece;
-        const int32_t k1 = std::min(b + len, k0 + piece);
-        row_order.push_back({i, k0, k1, (int32_t)slots++});
+// Row-segment tables for `n_panels` column panels.  colidx (host copy) is only needed when
+// n_panels > 1.
+void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vector<int32_t>& rowptr,
+                    const int32_t* colidx, int32_t n_panels, int32_t seg_len) {
+  const int32_t P = std::max(n_panels, 1);
+  const int64_t width = ceil_div(std::max(n_cols, 1), P);
+  ts->n_panels = P;
+  std::vector<std::vector<Task>> per_panel((size_t)P);
+  std::vector<std::vector<FixRow>> per_panel_fix((size_t)P);
+  std::vector<int64_t> slots((size_t)P, 0);
+  std::vector<int32_t> cut((size_t)P + 1);
+  for (int32_t i = 0; i < n_rows; ++i) {
+    const int32_t b = rowptr[i], e = rowptr[(size_t)i + 1];
+    cut[0] = b;
+    cut[(size_t)P] = e;
+    for (int32_t p = 1; p < P; ++p)
+      cut[p] = (int32_t)(std::lower_bound(colidx + cut[p - 1], colidx + e, (int32_t)std::min<int64_t>(p * width, n_cols)) - colidx);
+    int32_t first = -1, last = -1;
+    for (int32_t p = 0; p < P; ++p)
+      if (cut[(size_t)p + 1] > cut[p]) { if (first < 0) first = p; last = p; }
+    if (first < 0) first = last = 0;  // empty row: one empty task that still writes beta*Y / zeros
+    for (int32_t p = first; p <= last; ++p) {
+      const int32_t lo = cut[p], len = cut[(size_t)p + 1] - lo;
+      if (len == 0 && !(p == first && first == last)) continue;
+      const uint32_t flags = (p == first ? kTaskFirst : 0u) | (p == last ? kTaskLast : 0u);
+      if (len <= seg_len) {
+        per_panel[p].push_back({i, lo, (uint32_t)len | flags, -1});
+      } else {
+        const int32_t nseg = (int32_t)ceil_div(len, seg_len);
+        const int32_t piece = (int32_t)ceil_div(len, nseg);
+        per_panel_fix[p].push_back({i, (int32_t)slots[p], nseg, flags});
+        for (int32_t s = 0; s < nseg; ++s) {
+          const int32_t k0 = lo + s * piece;
+          const int32_t k1 = std::min(lo + len, k0 + piece);
+          per_panel[p].push_back({i, k0, (uint32_t)(k1 - k0), (int32_t)slots[p]++});
+        }
       }
     }
   }
-  o->n_slots = slots;
-  // counting sort by length, longest first, row order kept inside a length
-  std::vector<int64_t> start((size_t)seg_len + 2, 0);
-  for (const Task& t : row_order) start[(size_t)(seg_len - (t.k1 - t.k0)) + 1]++;
-  for (int32_t l = 0; l <= seg_len; ++l) start[(size_t)l + 1] += start[l];
-  o->tasks.resize(row_order.size());
-  for (const Task& t : row_order) o->tasks[(size_t)start[(size_t)(seg_len - (t.k1 - t.k0))]++] = t;
-  for (int i = 0; i < kLenClasses; ++i) {
-    const int32_t thr = 8 << i;
-    // tasks are sorted descending: count of length >= thr by binary search
-    int64_t lo = 0, hi = (int64_t)o->tasks.size();
-    while (lo < hi) {
-      const int64_t mid = (lo + hi) / 2;
-      if (o->tasks[(size_t)mid].k1 - o->tasks[(size_t)mid].k0 >= thr) lo = mid + 1; else hi = mid;
+  ts->tasks.clear();
+  ts->fix.clear();
+  ts->task_begin.assign((size_t)P + 1, 0);
+  ts->fix_begin.assign((size_t)P + 1, 0);
+  ts->cnt_ge.assign((size_t)P, {});
+  ts->n_slots = 0;
+  std::vector<int64_t> start;
+  for (int32_t p = 0; p < P; ++p) {
+    const std::vector<Task>& in = per_panel[p];
+    // counting sort by length, longest first, row order kept inside a length
+    start.assign((size_t)seg_len + 2, 0);
+    for (const Task& t : in) start[(size_t)(seg_len - (int32_t)(t.len_flags & kTaskLenMask)) + 1]++;
+    for (int32_t l = 0; l <= seg_len; ++l) start[(size_t)l + 1] += start[l];
+    const size_t base = ts->tasks.size();
+    ts->tasks.resize(base + in.size());
+    for (const Task& t : in)
+      ts->tasks[base + (size_t)start[(size_t)(seg_len - (int32_t)(t.len_flags & kTaskLenMask))]++] = t;
+    for (int i = 0; i < kLenClasses; ++i) {
+      const uint32_t thr = 8u << i;
+      int64_t lo = 0, hi = (int64_t)in.size();  // descending lengths: count of length >= thr
+      while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if ((ts->tasks[base + (size_t)mid].len_flags & kTaskLenMask) >= thr) lo = mid + 1; else hi = mid;
+      }
+      ts->cnt_ge[p][i] = lo;
     }
-    o->cnt_ge[i] = lo;
+    ts->task_begin[(size_t)p + 1] = (int64_t)ts->tasks.size();
+    ts->fix.insert(ts->fix.end(), per_panel_fix[p].begin(), per_panel_fix[p].end());
+    ts->fix_begin[(size_t)p + 1] = (int64_t)ts->fix.size();
+    ts->n_slots = std::max(ts->n_slots, slots[p]);
+    std::vector<Task>().swap(per_panel[p]);
   }
+}
+
+int pow2_floor(int64_t x) {
+  int p = 1;
+  while ((int64_t)p * 2 <= x) p <<= 1;
+  return p;
+}
+
+// Number of column panels: enough that one panel of the gathered operand (at a reference width
+// of 128 floats) is about 24 MB, but no more than the average row length affords -- every panel
+// costs one more read-modify-write of the output.
+int32_t choose_panels(int32_t n_rows, int32_t n_cols, int64_t nnz) {
+  if (const char* e = std::getenv("MGGCN_PANELS")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 64) return v;
+  }
+  if (n_rows <= 0 || nnz <= 0) return 1;
+  const int64_t x_ref = (int64_t)n_cols * 512;
+  int64_t by_cache = 1;
+  while (by_cache * (24ll << 20) < x_ref) by_cache <<= 1;
+  const int64_t by_degree = pow2_floor(std::max<int64_t>(1, nnz / n_rows / 16));
+  return (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min(by_cache, by_degree), 32));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -133,15 +197,31 @@ __device__ inline void store_out(float* __restrict__ dst, int nf, const float (&
   }
 }
 
-template <int VW, int LPR, int GPT>
+// Whole-vector load of VW floats.  The tail lane of a row may read up to VW-1 floats past F:
+// they lie inside the row's leading dimension (ld is a multiple of VW on this path) and only
+// feed accumulator components that are never stored.
+template <int VW>
+__device__ inline void load_vec(const float* __restrict__ p, float (&x)[VW]) {
+  if constexpr (VW == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+  } else if constexpr (VW == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    x[0] = t.x; x[1] = t.y;
+  } else {
+    x[0] = p[0];
+  }
+}
+
+template <int VW, int LPR, int GPT, int UMAX>
 __global__ __launch_bounds__(kThreads) void spmm_tasks(
     const Task* __restrict__ tasks, int64_t ntasks, const int32_t* __restrict__ colidx,
-    const float* __restrict__ val, const float* __restrict__ X, int64_t ldx, int F, int n_chunks,
+    const float* __restrict__ val, const float* __restrict__ X, uint32_t ldx_bytes, int F, int n_chunks,
     float beta, int epi, float* __restrict__ Y, int64_t ldy, float* __restrict__ partial,
     int64_t ldp) {
   constexpr int TEAM = LPR * GPT;
   constexpr int TPW = 64 / TEAM;
-  constexpr int U = LPR < 8 ? LPR : 8;
+  constexpr int U = LPR < UMAX ? LPR : UMAX;
   static_assert(TEAM <= 64 && TPW >= 1, "team must fit a wavefront");
 
   const int chunk = (int)(blockIdx.x % (unsigned)n_chunks);
@@ -152,54 +232,78 @@ __global__ __launch_bounds__(kThreads) void spmm_tasks(
   const int team_base = team * TEAM;
   const int64_t t = (tb * (kThreads / 64) + wave) * TPW + team;
 
-  Task task = {0, 0, 0, -1};
+  Task task = {0, 0, 0u, -1};
   const bool has_task = t < ntasks;
   if (has_task) task = tasks[t];
-  const int len = task.k1 - task.k0;
+  const int len = (int)(task.len_flags & kTaskLenMask);
 
-  // longest task in this wavefront (uniform loop bound, so the shuffles below stay convergent)
-  int maxlen = len;
+  // longest and shortest task of this wavefront: uniform loop bounds, so the shuffles below
+  // are executed by all lanes together
+  int maxlen = len, minlen = len;
 #pragma unroll
-  for (int d = TEAM; d < 64; d <<= 1) maxlen = max(maxlen, __shfl_xor(maxlen, d));
+  for (int d = TEAM; d < 64; d <<= 1) {
+    maxlen = max(maxlen, __shfl_xor(maxlen, d));
+    minlen = min(minlen, __shfl_xor(minlen, d));
+  }
   maxlen = __builtin_amdgcn_readfirstlane(maxlen);
+  minlen = __builtin_amdgcn_readfirstlane(minlen);
 
   const int f0 = chunk * (LPR * VW) + fl * VW;
   const int nf = min(VW, max(0, F - f0));
-  const float* __restrict__ xcol = X + f0;
+  const bool live = nf > 0;  // this lane covers at least one feature column
+  const char* __restrict__ xbase = reinterpret_cast<const char*>(X + f0);
+  const int32_t* __restrict__ cptr = colidx + task.k0 + tl;
+  const float* __restrict__ vptr = val + task.k0 + tl;
 
   float acc[VW];
+  float xs[U][VW];
 #pragma unroll
   for (int i = 0; i < VW; ++i) acc[i] = 0.f;
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int i = 0; i < VW; ++i) xs[u][i] = 0.f;
 
   int c = 0;
   float v = 0.f;
   if (tl < len) {
-    c = __builtin_nontemporal_load(colidx + task.k0 + tl);
-    v = __builtin_nontemporal_load(val + task.k0 + tl);
+    c = __builtin_nontemporal_load(cptr);
+    v = __builtin_nontemporal_load(vptr);
   }
   for (int base = 0; base < maxlen; base += TEAM) {
     int c_next = 0;
     float v_next = 0.f;
     if (base + TEAM + tl < len) {
-      c_next = __builtin_nontemporal_load(colidx + task.k0 + base + TEAM + tl);
-      v_next = __builtin_nontemporal_load(val + task.k0 + base + TEAM + tl);
+      c_next = __builtin_nontemporal_load(cptr + base + TEAM);
+      v_next = __builtin_nontemporal_load(vptr + base + TEAM);
     }
+    // full step: every team of the wavefront still has TEAM entries, nothing to predicate
+    const bool full = base + TEAM <= minlen;
     const int remaining = maxlen - base;  // uniform
-#pragma unroll
+#pragma unroll 1
     for (int j0 = 0; j0 < LPR; j0 += U) {
       if (j0 * GPT >= remaining) break;
-      float xs[U][VW];
+      int cj[U];
       float vs[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int e = (j0 + u) * GPT + g;  // entry of this TEAM-chunk handled by my group
-        const int cj = __shfl(c, team_base + e);
-        vs[u] = __shfl(v, team_base + e);
-        if (base + e < len && nf > 0) {
-          load_row<VW>(xcol + (int64_t)cj * ldx, nf, xs[u]);
-        } else {
+        const int src = team_base + (j0 + u) * GPT + g;  // entry handled by my lane group
+        cj[u] = __shfl(c, src);
+        vs[u] = __shfl(v, src);  // 0 beyond the task's end
+      }
+      if (full) {
+        if (live) {
+#pragma unroll
+          for (int u = 0; u < U; ++u)
+            load_vec<VW>(reinterpret_cast<const float*>(xbase + (uint64_t)(uint32_t)cj[u] * ldx_bytes), xs[u]);
+        }
+      } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
           for (int i = 0; i < VW; ++i) xs[u][i] = 0.f;
+          if (live && base + (j0 + u) * GPT + g < len)
+            load_vec<VW>(reinterpret_cast<const float*>(xbase + (uint64_t)(uint32_t)cj[u] * ldx_bytes), xs[u]);
         }
       }
 #pragma unroll
@@ -217,11 +321,12 @@ __global__ __launch_bounds__(kThreads) void spmm_tasks(
 #pragma unroll
     for (int i = 0; i < VW; ++i) acc[i] += __shfl_xor(acc[i], d);
 
-  if (has_task && g == 0 && nf > 0) {
+  if (has_task && g == 0 && live) {
     if (task.slot >= 0)
       store_out<VW>(partial + (int64_t)task.slot * ldp + f0, nf, acc, 0.f, MGGCN_EPI_NONE, false);
     else
-      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, acc, beta, epi, true);
+      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, acc, (task.len_flags & kTaskFirst) ? beta : 1.f,
+                    (task.len_flags & kTaskLast) ? epi : (int)MGGCN_EPI_NONE, true);
   }
 }
 
@@ -233,6 +338,8 @@ __global__ __launch_bounds__(kThreads) void spmm_fixup(const FixRow* __restrict_
   const int64_t r = blockIdx.x;
   if (r >= nfix) return;
   const FixRow fr = fix[r];
+  if (!(fr.flags & kTaskFirst)) beta = 1.f;
+  if (!(fr.flags & kTaskLast)) epi = MGGCN_EPI_NONE;
   for (int f = threadIdx.x; f < F; f += kThreads) {
     float s = 0.f;
     for (int k = 0; k < fr.nslots; ++k) s += partial[(int64_t)(fr.slot0 + k) * ldp + f];
@@ -266,9 +373,9 @@ int launch_one(const LaunchArgs& a) {
   const int64_t blocks = ceil_div(a.ntasks, teams_per_block) * a.n_chunks;
   MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "SpMM grid of %lld blocks too large",
                 (long long)blocks);
-  spmm_tasks<VW, LPR, GPT><<<(unsigned)blocks, kThreads, 0, a.stream>>>(
-      a.tasks, a.ntasks, a.colidx, a.val, a.X, a.ldx, a.F, a.n_chunks, a.beta, a.epi, a.Y, a.ldy,
-      a.partial, a.ldp);
+  spmm_tasks<VW, LPR, GPT, 8><<<(unsigned)blocks, kThreads, 0, a.stream>>>(
+      a.tasks, a.ntasks, a.colidx, a.val, a.X, (uint32_t)(a.ldx * 4), a.F, a.n_chunks, a.beta, a.epi, a.Y,
+      a.ldy, a.partial, a.ldp);
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
 }
@@ -319,21 +426,31 @@ int pow2_ceil(int x) {
   return p;
 }
 
-size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, Task** t0, FixRow** f0, Task** t1,
-                   FixRow** f1, float** partial, int64_t* ldp_out) {
+struct GraphCarve {
+  Task* tasks[2][2];   // [orientation][flat, panelled]
+  FixRow* fix[2][2];
+  float* partial;
+  int64_t ldp;
+};
+
+size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* out) {
   Carver c(ws);
-  Task* a = c.take<Task>(g->fwd.tasks.size() + 1);
-  FixRow* b = c.take<FixRow>(g->fwd.fix.size() + 1);
-  Task* a2 = nullptr;
-  FixRow* b2 = nullptr;
-  if (!g->symmetric) {
-    a2 = c.take<Task>(g->bwd.tasks.size() + 1);
-    b2 = c.take<FixRow>(g->bwd.fix.size() + 1);
+  GraphCarve gc = {};
+  int64_t slots = 0;
+  const Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
+  for (int o = 0; o < 2; ++o) {
+    if (!os[o]) continue;
+    const TaskSet* sets[2] = {&os[o]->flat, &os[o]->panelled};
+    for (int k = 0; k < 2; ++k) {
+      if (sets[k]->n_panels == 0) continue;
+      gc.tasks[o][k] = c.take<Task>(sets[k]->tasks.size() + 1);
+      gc.fix[o][k] = c.take<FixRow>(sets[k]->fix.size() + 1);
+      slots = std::max(slots, sets[k]->n_slots);
+    }
   }
-  const int64_t ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
-  const int64_t slots = std::max(g->fwd.n_slots, g->symmetric ? 0 : g->bwd.n_slots);
-  float* p = c.take<float>((size_t)(slots * ldp) + 64);
-  if (t0) { *t0 = a; *f0 = b; *t1 = a2; *f1 = b2; *partial = p; *ldp_out = ldp; }
+  gc.ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
+  gc.partial = c.take<float>((size_t)(slots * gc.ldp) + 64);
+  if (out) *out = gc;
   return c.off;
 }
 
@@ -346,7 +463,8 @@ extern "C" {
 
 int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, const int32_t* colidx,
                        const float* val, const int32_t* rowptr_t, const int32_t* colidx_t,
-                       const float* val_t, int32_t seg_len, void* stream, mggcn_graph** out) {
+                       const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
+                       mggcn_graph** out) {
   MGGCN_REQUIRE(out != nullptr, MGGCN_E_INVALID_ARG, "out is NULL");
   *out = nullptr;
   MGGCN_REQUIRE(n_rows >= 0 && n_cols >= 0, MGGCN_E_INVALID_ARG, "negative matrix size %d x %d",
@@ -356,6 +474,8 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
                 "seg_len %d outside [0, 2^20]", seg_len);
   MGGCN_REQUIRE(rowptr_t != nullptr || n_rows == n_cols, MGGCN_E_INVALID_ARG,
                 "a %d x %d matrix cannot be declared symmetric: pass its transpose", n_rows, n_cols);
+  MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 64, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 64]",
+                n_panels);
   if (seg_len == 0) {
     seg_len = kDefaultSegLen;
     if (const char* e = std::getenv("MGGCN_SEG_LEN")) {
@@ -370,10 +490,12 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
   g->symmetric = (rowptr_t == nullptr);
   g->seg_len = seg_len;
+  g->panel_min_bytes = n_panels > 1 ? 0 : (24ll << 20);
   if (const char* e = std::getenv("MGGCN_CHUNK_LANES")) {
     const int v = std::atoi(e);
     if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) g->chunk_lanes = v;
   }
+  if (const char* e = std::getenv("MGGCN_PANEL_MIN_MB")) g->panel_min_bytes = (int64_t)std::atoi(e) << 20;
 
   auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const int32_t* rp, const int32_t* ci,
                    const float* va) -> int {
@@ -386,7 +508,15 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
       MGGCN_REQUIRE(h[(size_t)i + 1] >= h[i], MGGCN_E_BAD_CSR, "rowptr decreases at row %d", i);
     o->nnz = h[nr];
     MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
-    analyse(o, h, seg_len);
+    build_task_set(&o->flat, nr, nc, h, nullptr, 1, seg_len);
+    const int32_t P = n_panels > 0 ? n_panels : choose_panels(nr, nc, o->nnz);
+    if (P > 1) {
+      // panel cuts need the column indices: one read-back, setup only
+      std::vector<int32_t> hc((size_t)o->nnz);
+      MGGCN_HIP(hipMemcpyAsync(hc.data(), ci, sizeof(int32_t) * (size_t)o->nnz, hipMemcpyDeviceToHost, s));
+      MGGCN_HIP(hipStreamSynchronize(s));
+      build_task_set(&o->panelled, nr, nc, h, hc.data(), P, seg_len);
+    }
     return MGGCN_OK;
   };
   int rc = setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val);
@@ -402,7 +532,7 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
 
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max) {
   if (!g || F_max < 0) return 0;
-  return carve_graph(g, F_max, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+  return carve_graph(g, F_max, nullptr, nullptr);
 }
 
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, void* stream) {
@@ -413,22 +543,28 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
   MGGCN_REQUIRE(ws_bytes >= need, MGGCN_E_WORKSPACE, "workspace too small: %zu bytes given, %zu needed",
                 ws_bytes, need);
   hipStream_t s = as_stream(stream);
-  Task *t0, *t1;
-  FixRow *f0, *f1;
-  carve_graph(g, F_max, ws, &t0, &f0, &t1, &f1, &g->d_partial, &g->ldp);
-  auto upload = [&](Orientation* o, Task* dt, FixRow* df) -> int {
-    o->d_tasks = dt;
-    o->d_fix = df;
-    if (!o->tasks.empty())
-      MGGCN_HIP(hipMemcpyAsync(dt, o->tasks.data(), sizeof(Task) * o->tasks.size(), hipMemcpyHostToDevice, s));
-    if (!o->fix.empty())
-      MGGCN_HIP(hipMemcpyAsync(df, o->fix.data(), sizeof(FixRow) * o->fix.size(), hipMemcpyHostToDevice, s));
-    return MGGCN_OK;
-  };
-  int rc = upload(&g->fwd, t0, f0);
-  if (!rc && !g->symmetric) rc = upload(&g->bwd, t1, f1);
-  if (rc) return rc;
+  GraphCarve gc;
+  carve_graph(g, F_max, ws, &gc);
+  Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
+  for (int o = 0; o < 2; ++o) {
+    if (!os[o]) continue;
+    TaskSet* sets[2] = {&os[o]->flat, &os[o]->panelled};
+    for (int k = 0; k < 2; ++k) {
+      TaskSet* ts = sets[k];
+      if (ts->n_panels == 0) continue;
+      ts->d_tasks = gc.tasks[o][k];
+      ts->d_fix = gc.fix[o][k];
+      if (!ts->tasks.empty())
+        MGGCN_HIP(hipMemcpyAsync(ts->d_tasks, ts->tasks.data(), sizeof(Task) * ts->tasks.size(),
+                                 hipMemcpyHostToDevice, s));
+      if (!ts->fix.empty())
+        MGGCN_HIP(hipMemcpyAsync(ts->d_fix, ts->fix.data(), sizeof(FixRow) * ts->fix.size(),
+                                 hipMemcpyHostToDevice, s));
+    }
+  }
   MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
+  g->d_partial = gc.partial;
+  g->ldp = gc.ldp;
   g->F_bound = F_max;
   g->bound = true;
   return MGGCN_OK;
@@ -439,6 +575,15 @@ int mggcn_graph_destroy(mggcn_graph* g) {
   return MGGCN_OK;
 }
 
+int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
+  MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
+  const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
+  const bool use_panels = o.panelled.n_panels > 1 &&
+                          (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
+  return use_panels ? o.panelled.n_panels : 1;
+}
+
 int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_t F, float beta,
                int epilogue, float* Y, int64_t ldy, void* stream) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
@@ -446,6 +591,8 @@ int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_
   MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
   MGGCN_REQUIRE(ldx >= F && ldy >= F, MGGCN_E_INVALID_ARG, "leading dimension (ldx %lld, ldy %lld) < F %d",
                 (long long)ldx, (long long)ldy, F);
+  MGGCN_REQUIRE(ldx < ((int64_t)1 << 30), MGGCN_E_OVERFLOW, "ldx %lld: a row of X must be shorter than 4 GiB",
+                (long long)ldx);
   MGGCN_REQUIRE(beta == 0.f || beta == 1.f, MGGCN_E_INVALID_ARG, "beta must be 0 or 1");
   MGGCN_REQUIRE(epilogue == MGGCN_EPI_NONE || epilogue == MGGCN_EPI_RELU || epilogue == MGGCN_EPI_RELU_MASK,
                 MGGCN_E_INVALID_ARG, "unknown epilogue %d", epilogue);
@@ -466,31 +613,39 @@ int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_
   const int n_chunks = (int)ceil_div(F, lpr * vw);
   const int gpt_max = 64 / lpr;
 
+  // Column panels pay when the gathered operand is much larger than the caches; the in-place
+  // ReLU' mask needs the old Y at every write, which only the single-panel form provides.
+  const bool use_panels = o.panelled.n_panels > 1 && epilogue != MGGCN_EPI_RELU_MASK &&
+                          (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
+  const TaskSet& ts = use_panels ? o.panelled : o.flat;
+
   LaunchArgs a;
   a.colidx = o.colidx; a.val = o.val; a.X = X; a.ldx = ldx; a.F = F; a.n_chunks = n_chunks;
   a.beta = beta; a.epi = epilogue; a.Y = Y; a.ldy = ldy; a.partial = g->d_partial; a.ldp = g->ldp;
   a.stream = as_stream(stream);
 
-  // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
-  const int64_t ntasks = (int64_t)o.tasks.size();
   int top = 0;
   while ((1 << (top + 1)) <= gpt_max) ++top;  // gpt_max = 1 << top
-  int64_t begin = 0;
-  for (int i = top; i >= 0; --i) {
-    const int64_t end = (i == 0) ? ntasks : o.cnt_ge[i];  // length >= 8 << i  => gpt = 1 << i
-    if (end > begin) {
-      a.tasks = o.d_tasks + begin;
-      a.ntasks = end - begin;
-      const int rc = launch_any(vw, lpr, 1 << i, a);
-      if (rc) return rc;
-      begin = end;
+  for (int32_t p = 0; p < ts.n_panels; ++p) {
+    // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
+    const int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
+    int64_t begin = 0;
+    for (int i = top; i >= 0; --i) {
+      const int64_t end = (i == 0) ? ntasks : ts.cnt_ge[p][i];  // length >= 8 << i  => gpt = 1 << i
+      if (end > begin) {
+        a.tasks = ts.d_tasks + ts.task_begin[p] + begin;
+        a.ntasks = end - begin;
+        const int rc = launch_any(vw, lpr, 1 << i, a);
+        if (rc) return rc;
+        begin = end;
+      }
     }
-  }
-  if (!o.fix.empty()) {
-    spmm_fixup<<<(unsigned)o.fix.size(), kThreads, 0, a.stream>>>(o.d_fix, (int64_t)o.fix.size(),
-                                                                  g->d_partial, g->ldp, F, beta,
-                                                                  epilogue, Y, ldy);
-    MGGCN_LAUNCH_CHECK();
+    const int64_t nfix = ts.fix_begin[(size_t)p + 1] - ts.fix_begin[p];
+    if (nfix > 0) {
+      spmm_fixup<<<(unsigned)nfix, kThreads, 0, a.stream>>>(ts.d_fix + ts.fix_begin[p], nfix, g->d_partial,
+                                                           g->ldp, F, beta, epilogue, Y, ldy);
+      MGGCN_LAUNCH_CHECK();
+    }
   }
   return MGGCN_OK;
 }

@@ -74,10 +74,11 @@ def test_argument_errors_need_no_device(B):
     assert L.mggcn_csr_transpose(4, 4, 3, 256, 256, 256, 256, 256, 256, 256, 16, None) == B.E_WORKSPACE
     # graph / spmm
     h = C.c_void_p(None)
-    assert L.mggcn_graph_create(-3, 3, 256, 256, 256, None, None, None, 0, None, C.byref(h)) == B.E_INVALID_ARG
-    assert L.mggcn_graph_create(3, 4, 256, 256, 256, None, None, None, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create(-3, 3, 256, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create(3, 4, 256, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
     assert "symmetric" in B.last_error()
-    assert L.mggcn_graph_create(3, 3, None, 256, 256, None, None, None, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create(3, 3, None, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create(3, 3, 256, 256, 256, None, None, None, 0, 65, None, C.byref(h)) == B.E_INVALID_ARG
     assert L.mggcn_spmm(None, 0, 256, 4, 4, 0.0, 0, 256, 4, None) == B.E_INVALID_ARG
     # loss / relu
     assert L.mggcn_softmax_ce(0, 4, 256, 4, 256, 256, 256, 4, 256, 1024, None) == B.E_INVALID_ARG

@@ -293,6 +293,31 @@ def test_spmm_is_deterministic_and_segment_length_invariant(mg, dev, ref, spmm_g
         assert_rows_close(mg.mggcn_spmm(G2, mg.OP_N, Xd).cpu().numpy(), want, what=f"seg_len={seg}")
 
 
+@pytest.mark.parametrize("name", ["adversarial", "powerlaw", "rmat"])
+@pytest.mark.parametrize("P,seg", [(2, 0), (7, 0), (16, 16), (64, 0)])
+def test_spmm_column_panels(mg, dev, ref, spmm_graphs, name, P, seg):
+    """Column-panel passes (the stage loop C += A^{ij} H^j on one GPU) give the unsplit product,
+    with beta, the fused ReLU and cut rows handled once per row."""
+    say(f"[spmm panels] graph={name} P={P} seg_len={seg}")
+    g, rp, ci, val, _ = spmm_graphs[name]
+    n = g.n_rows
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128, seg_len=seg, n_panels=P)
+    v64 = val.astype(np.float64)
+    for F in (41, 128):
+        X = wl.normal_f32(55, F, (n, F))
+        Y0 = wl.normal_f32(56, F, (n, F))
+        want = ref.spmm(ref.OP_N, n, n, rp, ci, v64, X.astype(np.float64))
+        got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy()
+        assert_rows_close(got, want, what=f"panels F={F}")
+        assert np.array_equal(got, mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy())
+        got_relu = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), epilogue=mg.EPI_RELU).cpu().numpy()
+        assert np.array_equal(got_relu, np.maximum(got, 0.0))
+        acc = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), beta=1.0, Y=to_dev(Y0, dev)).cpu().numpy()
+        assert_rows_close(acc, want + Y0.astype(np.float64), what=f"panels beta F={F}")
+        masked = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev), epilogue=mg.EPI_RELU_MASK, Y=to_dev(Y0, dev)).cpu().numpy()
+        assert_rows_close(masked, np.where(Y0 > 0, want, 0.0), what=f"panels mask F={F}")
+
+
 # ----------------------------------------------------------------------------------------------
 # a1 / a7 / a8: GeMM
 # ----------------------------------------------------------------------------------------------
