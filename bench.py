@@ -28,7 +28,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 
 # HBM bytes per launch of the F=128 SpMM measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # filled in from profiles/ once measured; None = not measured.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = 2_910_116_677  # per panel launch; profiles/spmm_medium_F128_pmc.md
 
 
 def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
@@ -44,6 +44,9 @@ def main() -> int:
     ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seg-len", type=int, default=0)
+    ap.add_argument("--profile-spmm", type=int, default=0, metavar="N",
+                    help="counter-collection mode: N forward SpMM calls at the epoch's widest width plus one "
+                         "1 GiB device copy of known size (calibration), then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -80,6 +83,21 @@ def main() -> int:
     model = mg.Model(graph, dims)
     torch.cuda.synchronize()
     setup_s = time.time() - t0
+
+    if args.profile_spmm > 0:
+        F = max(dims[l] if model.order(l) == mg.ORDER_SPMM_FIRST else dims[l + 1] for l in range(L))
+        src = torch.randn((n, F), device=dev)
+        dst = torch.empty((n, F), device=dev)
+        for _ in range(args.profile_spmm):
+            mg.mggcn_spmm(graph, mg.OP_N, src, epilogue=mg.EPI_RELU, Y=dst)
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)  # 1 GiB
+        b = torch.empty_like(a)
+        b.copy_(a)  # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "profile-spmm", "calls": args.profile_spmm, "F": F, "n": n, "nnz": nnz,
+                          "panels": graph.panels(F), "algorithmic_bytes_per_call": spmm_bytes(nnz, n, F),
+                          "copy_bytes_each_way": 4 << 28}))
+        return 0
 
     WG = [torch.empty_like(w) for w in Ws]
     loss = torch.empty(1, dtype=torch.float32, device=dev)
