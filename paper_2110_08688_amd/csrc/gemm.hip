@@ -4,7 +4,7 @@
 //   C = epilogue( op(A) op(B) + beta C )
 //
 // One kernel template.  A workgroup of 4 wavefronts owns a BM x BN tile of C and walks K in
-// steps of 16.  Both operand tiles are staged through LDS in k-major order (As[k][m], Bs[k][n])
+// steps of 32 (16 for a short inner dimension).  Both operand tiles are staged through LDS in k-major order (As[k][m], Bs[k][n])
 // whatever their layout in memory, because that is the order v_mfma_f32_32x32x2_f32 wants its
 // fragments in: lane l feeds A[m = l%32][k = l/32] and B[k = l/32][n = l%32], so a fragment is
 // 32 consecutive floats of one LDS row and is read without bank conflicts.  The next k-step's
@@ -22,23 +22,25 @@ namespace mggcn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int BK = 16;
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 
 // Tile of an operand whose memory rows run along K (A not transposed, or B transposed):
 // R rows x BK, staged as 4 consecutive k per thread.
-template <int R>
+template <int R, int BK>
 struct KContig {
-  static constexpr int kPasses = R / 64;
+  static constexpr int kThreadsPerRow = BK / 4;
+  static constexpr int kRowsPerPass = kThreads / kThreadsPerRow;
+  static constexpr int kPasses = R / kRowsPerPass;
   static constexpr int kRegs = kPasses * 4;
+  static_assert(kPasses >= 1 && R % kRowsPerPass == 0, "tile does not divide over the workgroup");
   __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t row0,
                                      int64_t row_end, int64_t k0, int64_t k_end, bool vec,
                                      float (&reg)[kRegs]) {
-    const int r = threadIdx.x >> 2, kq = threadIdx.x & 3;
+    const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
-      const int64_t row = row0 + p * 64 + r;
+      const int64_t row = row0 + p * kRowsPerPass + r;
       const int64_t k = k0 + 4 * kq;
       const float* ptr = src + row * ld + k;
       if (row < row_end && vec && k + 3 < k_end) {
@@ -52,22 +54,23 @@ struct KContig {
   }
   template <int LD>
   __device__ static inline void store(float (*S)[LD], const float (&reg)[kRegs]) {
-    const int r = threadIdx.x >> 2, kq = threadIdx.x & 3;
+    const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
 #pragma unroll
     for (int p = 0; p < kPasses; ++p)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) S[4 * kq + i][p * 64 + r] = reg[p * 4 + i];
+      for (int i = 0; i < 4; ++i) S[4 * kq + i][p * kRowsPerPass + r] = reg[p * 4 + i];
   }
 };
 
 // Tile of an operand whose memory rows run along the tile's M/N side (A transposed, or B not
 // transposed): BK x R, 4 consecutive m (or n) per thread.
-template <int R>
+template <int R, int BK>
 struct MContig {
   static constexpr int kThreadsPerRow = R / 4;
   static constexpr int kRowsPerPass = kThreads / kThreadsPerRow;
   static constexpr int kPasses = BK / kRowsPerPass;
   static constexpr int kRegs = kPasses * 4;
+  static_assert(kPasses >= 1 && BK % kRowsPerPass == 0, "tile does not divide over the workgroup");
   __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t col0,
                                      int64_t col_end, int64_t k0, int64_t k_end, bool vec,
                                      float (&reg)[kRegs]) {
@@ -105,7 +108,7 @@ __device__ inline float gemm_epilogue(float acc, float old, float beta, int epi)
 }
 
 // WM x WN wavefronts tile the BM x BN block; each wavefront holds TM x TN accumulators of 32x32.
-template <int BM, int BN, int WM, int WN, bool TA, bool TB>
+template <int BM, int BN, int BK, int WM, int WN, bool TA, bool TB>
 __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int64_t K,
                                                        const float* __restrict__ A, int64_t lda,
                                                        const float* __restrict__ B, int64_t ldb,
@@ -116,10 +119,13 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int6
   static_assert(WM * WN == kThreads / 64, "four wavefronts");
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
   static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
-  constexpr int LDA = BM + (TA ? 4 : 2);
-  constexpr int LDB = BN + (TB ? 2 : 4);
-  using LoadA = typename std::conditional<TA, MContig<BM>, KContig<BM>>::type;
-  using LoadB = typename std::conditional<TB, KContig<BN>, MContig<BN>>::type;
+  // row padding: 16-byte aligned rows for the vector stores of an m-contiguous operand; for the
+  // transposing scalar stores of a k-contiguous one, the stride that spreads the BK/4 k-quads of a
+  // half-wavefront over distinct banks
+  constexpr int LDA = BM + (TA ? 4 : 32 / BK);
+  constexpr int LDB = BN + (TB ? 32 / BK : 4);
+  using LoadA = typename std::conditional<TA, MContig<BM, BK>, KContig<BM, BK>>::type;
+  using LoadB = typename std::conditional<TB, KContig<BN, BK>, MContig<BN, BK>>::type;
 
   __shared__ __attribute__((aligned(16))) float As[BK][LDA];
   __shared__ __attribute__((aligned(16))) float Bs[BK][LDB];
@@ -193,21 +199,30 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int6
     }
 }
 
+// Sum of the split-K partial products, in a fixed order: 8 lanes share one output element, each
+// adds every 8th split, then the 8 are folded by a shuffle tree.
 __global__ __launch_bounds__(kThreads) void gemm_reduce_splits(int64_t M, int64_t N, int splits,
                                                                 const float* __restrict__ partial,
                                                                 float* __restrict__ C, int64_t ldc,
                                                                 float beta, int epi) {
-  const int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (idx >= M * N) return;
+  constexpr int ZL = 8;
+  const int zl = threadIdx.x % ZL;
+  const int64_t idx = ((int64_t)blockIdx.x * kThreads + threadIdx.x) / ZL;
+  const bool live = idx < M * N;
   float s = 0.f;
-  for (int z = 0; z < splits; ++z) s += partial[(int64_t)z * M * N + idx];
-  float* dst = C + (idx / N) * ldc + (idx % N);
-  const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
-  *dst = gemm_epilogue(s, old, beta, epi);
+  if (live)
+    for (int z = zl; z < splits; z += ZL) s += partial[(int64_t)z * M * N + idx];
+#pragma unroll
+  for (int d = 1; d < ZL; d <<= 1) s += __shfl_xor(s, d);
+  if (live && zl == 0) {
+    float* dst = C + (idx / N) * ldc + (idx % N);
+    const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
+    *dst = gemm_epilogue(s, old, beta, epi);
+  }
 }
 
 struct Shape {
-  int bm, bn;
+  int bm, bn, bk;
   int64_t tiles_m, tiles_n;
   int splits;
   int64_t k_per_split;
@@ -217,13 +232,15 @@ Shape plan_shape(int opA, int64_t M, int64_t N, int64_t K) {
   Shape s;
   s.bm = 128;
   s.bn = (N > 64) ? 128 : 64;
+  s.bk = (K >= 64) ? 32 : 16;
+  const int BK = s.bk;
   s.tiles_m = ceil_div(std::max<int64_t>(M, 1), s.bm);
   s.tiles_n = ceil_div(std::max<int64_t>(N, 1), s.bn);
   s.splits = 1;
   s.k_per_split = std::max<int64_t>(align_up((size_t)std::max<int64_t>(K, 1), BK), BK);
   if (opA == MGGCN_OP_T && K > 4096) {
     const int64_t tiles = s.tiles_m * s.tiles_n;
-    int64_t want = ceil_div(1024, tiles);
+    int64_t want = ceil_div(768, tiles);  // about three workgroups per CU
     want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
     want = std::max<int64_t>(want, 1);
     s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
@@ -232,7 +249,7 @@ Shape plan_shape(int opA, int64_t M, int64_t N, int64_t K) {
   return s;
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int BK, int WM, int WN>
 int launch_ops(int opA, int opB, const Shape& s, int64_t M, int64_t N, int64_t K, const float* A,
                int64_t lda, const float* B, int64_t ldb, float* C, int64_t ldc, float beta, int epi,
                float* partial, int vecA, int vecB, hipStream_t st) {
@@ -241,7 +258,7 @@ int launch_ops(int opA, int opB, const Shape& s, int64_t M, int64_t N, int64_t K
                 (long long)s.tiles_n, s.splits);
   dim3 grid((unsigned)s.tiles_m, (unsigned)s.tiles_n, (unsigned)s.splits);
 #define MGGCN_GEMM_LAUNCH(TA, TB)                                                                     \
-  gemm_mfma<BM, BN, WM, WN, TA, TB><<<grid, kThreads, 0, st>>>(M, N, K, A, lda, B, ldb, C, ldc, beta, \
+  gemm_mfma<BM, BN, BK, WM, WN, TA, TB><<<grid, kThreads, 0, st>>>(M, N, K, A, lda, B, ldb, C, ldc, beta, \
                                                                epi, s.k_per_split, partial, vecA, vecB)
   if (opA == MGGCN_OP_N && opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(false, false);
   else if (opA == MGGCN_OP_T && opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(true, false);
@@ -300,16 +317,16 @@ int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A
   const int vecA = (aligned(A, 16) && lda % 4 == 0) ? 1 : 0;
   const int vecB = (aligned(B, 16) && ldb % 4 == 0) ? 1 : 0;
   int rc;
-  if (s.bn == 128)
-    rc = launch_ops<128, 128, 2, 2>(opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial,
-                                    vecA, vecB, st);
-  else
-    rc = launch_ops<128, 64, 4, 1>(opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial,
-                                   vecA, vecB, st);
+#define MGGCN_GEMM_ARGS opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial, vecA, vecB, st
+  if (s.bn == 128 && s.bk == 32) rc = launch_ops<128, 128, 32, 2, 2>(MGGCN_GEMM_ARGS);
+  else if (s.bn == 128) rc = launch_ops<128, 128, 16, 2, 2>(MGGCN_GEMM_ARGS);
+  else if (s.bk == 32) rc = launch_ops<128, 64, 32, 4, 1>(MGGCN_GEMM_ARGS);
+  else rc = launch_ops<128, 64, 16, 4, 1>(MGGCN_GEMM_ARGS);
+#undef MGGCN_GEMM_ARGS
   if (rc) return rc;
   if (partial) {
-    gemm_reduce_splits<<<(unsigned)ceil_div(M * N, kThreads), kThreads, 0, st>>>(M, N, s.splits, partial,
-                                                                                C, ldc, beta, epilogue);
+    gemm_reduce_splits<<<(unsigned)ceil_div(M * N * 8, kThreads), kThreads, 0, st>>>(M, N, s.splits, partial,
+                                                                                    C, ldc, beta, epilogue);
     MGGCN_LAUNCH_CHECK();
   }
   return MGGCN_OK;

@@ -117,3 +117,178 @@ def test_medium_epoch(medium, ref):
         e = row_err(a.cpu().numpy(), b)
         say(f"[medium epoch] W_G[{l}] max row rel err {e.max():.3e}")
         assert e.max() <= 1e-4
+
+
+# ----------------------------------------------------------------------------------------------
+# Products-shaped "large" configuration: 2,449,029 vertices, ~126M entries, 100 -> 256 -> 256 -> 47
+# (first layer runs SpMM first, the other two GeMM first)
+# ----------------------------------------------------------------------------------------------
+
+@pytest.fixture(scope="module")
+def large(ref):
+    import torch
+
+    import paper_2110_08688_amd as mg
+
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS["large"]
+    t0 = time.time()
+    g = cfg.graph()
+    n = g.n_rows
+    say(f"[large] generated n={n} nnz={g.nnz} in {time.time() - t0:.1f}s")
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev))
+    rp, ci, rv = ref.csr_normalize(n, n, g.rowptr, g.colidx)
+    assert np.array_equal(rowptr.cpu().numpy(), rp) and np.array_equal(colidx.cpu().numpy(), ci)
+    assert np.array_equal(val.cpu().numpy().view(np.int32), rv.astype(np.float32).view(np.int32))
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=256)
+    return dict(mg=mg, dev=dev, cfg=cfg, n=n, rp=rp, ci=ci, v64=rv.astype(np.float32).astype(np.float64),
+                graph=graph)
+
+
+@pytest.mark.parametrize("F,ld", [(100, 112), (256, 256), (47, 48)])
+def test_large_spmm_all_rows(large, ref, F, ld):
+    import torch
+
+    m = large
+    mg, dev, n = m["mg"], m["dev"], m["n"]
+    say(f"[large spmm] F={F} ld={ld}")
+    Xp = wl.normal_f32(777, F, (n, ld))
+    Xd = torch.from_numpy(Xp).to(dev)
+    Yd = torch.zeros((n, ld), device=dev)
+    mg.mggcn_spmm(m["graph"], mg.OP_N, Xd[:, :F], Y=Yd[:, :F])
+    got = Yd.cpu().numpy()
+    t0 = time.time()
+    want = ref.spmm(ref.OP_N, n, n, m["rp"], m["ci"], m["v64"], Xp[:, :F].astype(np.float64))
+    e = row_err(got[:, :F], want)
+    say(f"[large spmm] oracle {time.time() - t0:.1f}s, max row rel err {e.max():.3e}")
+    assert e.max() <= 1e-4
+    assert np.all(got[:, F:] == 0)
+
+
+def test_large_epoch(large, ref):
+    import torch
+
+    m = large
+    mg, dev, n, cfg = m["mg"], m["dev"], m["n"], m["cfg"]
+    X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
+    model = mg.Model(m["graph"], cfg.dims)
+    assert [model.order(l) for l in range(3)] == [mg.ORDER_SPMM_FIRST, mg.ORDER_GEMM_FIRST, mg.ORDER_GEMM_FIRST]
+    Xd, Wd = torch.from_numpy(X).to(dev), [torch.from_numpy(w).to(dev) for w in Ws]
+    loss, WG = mg.mggcn_epoch(model, Xd, torch.from_numpy(labels).to(dev), Wd)
+    torch.cuda.synchronize()
+    say(f"[large epoch] gpu loss {loss.item():.7f}")
+    masks, H = [], Xd
+    for l in range(2):  # the device's own ReLU' decisions, same forward calls as inside the epoch
+        out = torch.empty((n, 256), device=dev)
+        mg.mggcn_layer_fwd(model, l, H, Wd[l], relu=True, H_out=out)
+        masks.append((out > 0).cpu().numpy().astype(np.uint8))
+        H = out
+    del H, out
+    t0 = time.time()
+    rl, rWG, _ = ref.epoch(n, m["rp"], m["ci"], m["v64"], X.astype(np.float64), labels,
+                           [w.astype(np.float64) for w in Ws], relu_masks=masks)
+    say(f"[large epoch] oracle {time.time() - t0:.1f}s loss {rl:.7f}")
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
+    for l, (a, b) in enumerate(zip(WG, rWG)):
+        e = row_err(a.cpu().numpy(), b)
+        say(f"[large epoch] W_G[{l}] max row rel err {e.max():.3e}")
+        assert e.max() <= 1e-4
+
+
+# ----------------------------------------------------------------------------------------------
+# skewed R-MAT graph (2^22 vertices, ~62M entries, 2.2M isolated vertices, hubs of ~94K entries)
+# ----------------------------------------------------------------------------------------------
+
+def test_rmat_spmm_all_rows(ref):
+    import torch
+
+    import paper_2110_08688_amd as mg
+
+    dev = torch.device("cuda:0")
+    g = wl.CONFIGS["rmat"].graph()
+    n = g.n_rows
+    say(f"[rmat] n={n} nnz={g.nnz} max degree {int(np.diff(g.rowptr).max())}")
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev))
+    rp, ci, rv = ref.csr_normalize(n, n, g.rowptr, g.colidx)
+    assert np.array_equal(rowptr.cpu().numpy(), rp) and np.array_equal(colidx.cpu().numpy(), ci)
+    assert np.array_equal(val.cpu().numpy().view(np.int32), rv.astype(np.float32).view(np.int32))
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=128)
+    X = wl.normal_f32(99, 128, (n, 128))
+    got = mg.mggcn_spmm(graph, mg.OP_N, torch.from_numpy(X).to(dev)).cpu().numpy()
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, rv.astype(np.float32).astype(np.float64), X.astype(np.float64))
+    e = row_err(got, want)
+    say(f"[rmat] max row rel err {e.max():.3e}")
+    assert e.max() <= 1e-4
+
+
+# ----------------------------------------------------------------------------------------------
+# one GPU's row block of a 1-D partition: 13.9M x 111M, ~200M entries, X 111M x 128 (56.8 GB on the
+# device).  The fp64 copy of X does not fit the host, so parity is on sampled output rows (4,096
+# random + the 64 longest), recomputed by the oracle from regenerated inputs.
+# ----------------------------------------------------------------------------------------------
+
+def test_row_block_spmm_sampled_rows(ref):
+    import torch
+
+    import paper_2110_08688_amd as mg
+
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS["block"]
+    t0 = time.time()
+    g = cfg.graph()
+    nr, nc = g.n_rows, g.n_cols
+    say(f"[block] generated {nr} x {nc}, nnz={g.nnz} in {time.time() - t0:.1f}s")
+    # stand-in global degrees: row degree = local count + 1, column degree = 1 + 8 * (count in block)
+    deg_row = (np.diff(g.rowptr) + 1).astype(np.int32)
+    deg_col = (1 + 8 * np.bincount(g.colidx, minlength=nc)).astype(np.int32)
+    rowptr, colidx, val = mg.mggcn_csr_normalize(nr, nc, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev),
+                                                 deg_row=torch.from_numpy(deg_row).to(dev),
+                                                 deg_col=torch.from_numpy(deg_col).to(dev))
+    rp, ci, rv = ref.csr_normalize(nr, nc, g.rowptr, g.colidx, deg_row=deg_row, deg_col=deg_col)
+    assert np.array_equal(rowptr.cpu().numpy(), rp) and np.array_equal(colidx.cpu().numpy(), ci)
+    assert np.array_equal(val.cpu().numpy().view(np.int32), rv.astype(np.float32).view(np.int32))
+    say(f"[block] normalised, nnz with diagonal {len(ci)}")
+    t = mg.mggcn_csr_transpose(nr, nc, rowptr, colidx, val)
+    graph = mg.Graph(nr, nc, rowptr, colidx, val, transpose=t, F_max=128)
+    F = 128
+    Xd = torch.empty((nc, F), dtype=torch.float32, device=dev)
+    chunk = 2_000_000
+    t0 = time.time()
+    for r0 in range(0, nc, chunk):  # counter-based generator: row r is elements [r*F, (r+1)*F) of the stream
+        r1 = min(nc, r0 + chunk)
+        Xd[r0:r1].copy_(torch.from_numpy(wl.normal_f32(cfg.seed + 0x100, 0, (r1 - r0, F), first=r0 * F)))
+    say(f"[block] X {nc} x {F} on the device in {time.time() - t0:.1f}s")
+    Yd = mg.mggcn_spmm(graph, mg.OP_N, Xd)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    deg = np.diff(rp)
+    rows = np.unique(np.concatenate([rng.integers(0, nr, 4096), np.argsort(deg)[-64:]]))
+    got = Yd[torch.from_numpy(rows).to(dev)].cpu().numpy()
+    v32 = rv.astype(np.float32).astype(np.float64)
+    worst = 0.0
+    for j, i in enumerate(rows):  # the definition, one sampled row at a time
+        cols = ci[rp[i]:rp[i + 1]]
+        acc = np.zeros(F)
+        for k, c in enumerate(cols):
+            x = wl.normal_f32(cfg.seed + 0x100, 0, (F,), first=int(c) * F).astype(np.float64)
+            acc += v32[rp[i] + k] * x
+        err = np.abs(got[j] - acc).max() / max(np.abs(acc).max(), 1e-300)
+        worst = max(worst, err)
+    say(f"[block] {len(rows)} sampled rows, max row rel err {worst:.3e}")
+    assert worst <= 1e-4
+    # transposed product on the same block (gradient of the dense operand): adjoint identity on a
+    # sampled pair, <A X, G> = <X, A^T G>, with G supported on the sampled rows only
+    Gd = torch.zeros((nr, F), dtype=torch.float32, device=dev)
+    Gs = wl.normal_f32(cfg.seed + 0x400, 0, (len(rows), F))
+    Gd[torch.from_numpy(rows).to(dev)] = torch.from_numpy(Gs).to(dev)
+    Td = mg.mggcn_spmm(graph, mg.OP_T, Gd)
+    lhs = float((Yd.double() * Gd.double()).sum().item())
+    rhs = 0.0
+    for r0 in range(0, nc, 4_000_000):  # fp64 dot product in slices: the operands are 57 GB each
+        r1 = min(nc, r0 + 4_000_000)
+        rhs += float((Xd[r0:r1].double() * Td[r0:r1].double()).sum().item())
+    say(f"[block] adjoint identity {lhs:.9e} vs {rhs:.9e}")
+    assert abs(lhs - rhs) <= 1e-5 * abs(lhs)

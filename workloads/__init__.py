@@ -184,7 +184,7 @@ CONFIGS = {
     # one GPU's 1/8 row block of a Papers-shaped graph, single layer 128-256
     "block": Config(
         "block", 3, (128, 256),
-        lambda s: row_block(13_900_000, 111_000_000, 200e6 - 13.9e6, 2.5, 20000.0, 1.6, s),
+        lambda s: row_block(13_900_000, 111_000_000, 200e6 - 13.9e6, 2.5, 20000.0, 0.909, s),
     ),
     # skewed R-MAT graph for the feature-width sweep
     "rmat": Config("rmat", 4, (128, 128), lambda s: rmat(22, 32_000_000, 0.57, 0.19, 0.19, s)),
