@@ -35,15 +35,34 @@ struct KContig {
   static constexpr int kRegs = kPasses * 4;
   static_assert(kPasses >= 1 && R % kRowsPerPass == 0, "tile does not divide over the workgroup");
   __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t row0,
-                                     int64_t row_end, int64_t k0, int64_t k_end, bool vec,
+                                     int64_t row_end, int64_t k0, int64_t k_end, int vec,
                                      float (&reg)[kRegs]) {
+    if (row0 + R <= row_end && k0 + BK <= k_end) {
+      const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
+#pragma unroll
+      for (int p = 0; p < kPasses; ++p) {  // interior tile: nothing to predicate
+        const float* ptr = src + (row0 + p * kRowsPerPass + r) * ld + k0 + 4 * kq;
+        if (vec == 4) {
+          const float4 t = *reinterpret_cast<const float4*>(ptr);
+          reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+        } else if (vec == 2) {  // rows aligned to 8 bytes only (odd multiples of two floats)
+          const float2 t = *reinterpret_cast<const float2*>(ptr);
+          const float2 u = *reinterpret_cast<const float2*>(ptr + 2);
+          reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = u.x; reg[p * 4 + 3] = u.y;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) reg[p * 4 + i] = ptr[i];
+        }
+      }
+      return;
+    }
     const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
       const int64_t row = row0 + p * kRowsPerPass + r;
       const int64_t k = k0 + 4 * kq;
       const float* ptr = src + row * ld + k;
-      if (row < row_end && vec && k + 3 < k_end) {
+      if (vec == 4 && row < row_end && k + 3 < k_end) {
         const float4 t = *reinterpret_cast<const float4*>(ptr);
         reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
       } else {
@@ -72,15 +91,34 @@ struct MContig {
   static constexpr int kRegs = kPasses * 4;
   static_assert(kPasses >= 1 && BK % kRowsPerPass == 0, "tile does not divide over the workgroup");
   __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t col0,
-                                     int64_t col_end, int64_t k0, int64_t k_end, bool vec,
+                                     int64_t col_end, int64_t k0, int64_t k_end, int vec,
                                      float (&reg)[kRegs]) {
+    if (col0 + R <= col_end && k0 + BK <= k_end) {
+      const int cq = threadIdx.x % kThreadsPerRow, kr = threadIdx.x / kThreadsPerRow;
+#pragma unroll
+      for (int p = 0; p < kPasses; ++p) {  // interior tile: nothing to predicate
+        const float* ptr = src + (k0 + p * kRowsPerPass + kr) * ld + col0 + 4 * cq;
+        if (vec == 4) {
+          const float4 t = *reinterpret_cast<const float4*>(ptr);
+          reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+        } else if (vec == 2) {  // rows aligned to 8 bytes only (odd multiples of two floats)
+          const float2 t = *reinterpret_cast<const float2*>(ptr);
+          const float2 u = *reinterpret_cast<const float2*>(ptr + 2);
+          reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = u.x; reg[p * 4 + 3] = u.y;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) reg[p * 4 + i] = ptr[i];
+        }
+      }
+      return;
+    }
     const int cq = threadIdx.x % kThreadsPerRow, kr = threadIdx.x / kThreadsPerRow;
 #pragma unroll
     for (int p = 0; p < kPasses; ++p) {
       const int64_t k = k0 + p * kRowsPerPass + kr;
       const int64_t col = col0 + 4 * cq;
       const float* ptr = src + k * ld + col;
-      if (k < k_end && vec && col + 3 < col_end) {
+      if (vec == 4 && k < k_end && col + 3 < col_end) {
         const float4 t = *reinterpret_cast<const float4*>(ptr);
         reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
       } else {
@@ -146,8 +184,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int6
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   float ra[LoadA::kRegs], rb[LoadB::kRegs];
-  LoadA::load(A, lda, m0, M, kb, ke, vecA != 0, ra);
-  LoadB::load(B, ldb, n0, N, kb, ke, vecB != 0, rb);
+  LoadA::load(A, lda, m0, M, kb, ke, vecA, ra);
+  LoadB::load(B, ldb, n0, N, kb, ke, vecB, rb);
 
   const int frow = lane >> 5, fcol = lane & 31;
   for (int64_t k0 = kb; k0 < ke; k0 += BK) {
@@ -155,8 +193,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t M, int64_t N, int6
     LoadB::template store<LDB>(Bs, rb);
     __syncthreads();
     if (k0 + BK < ke) {
-      LoadA::load(A, lda, m0, M, k0 + BK, ke, vecA != 0, ra);
-      LoadB::load(B, ldb, n0, N, k0 + BK, ke, vecB != 0, rb);
+      LoadA::load(A, lda, m0, M, k0 + BK, ke, vecA, ra);
+      LoadB::load(B, ldb, n0, N, k0 + BK, ke, vecB, rb);
     }
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
@@ -314,8 +352,12 @@ int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A
     partial = static_cast<float*>(ws);
   }
   hipStream_t st = as_stream(stream);
-  const int vecA = (aligned(A, 16) && lda % 4 == 0) ? 1 : 0;
-  const int vecB = (aligned(B, 16) && ldb % 4 == 0) ? 1 : 0;
+  auto vec_width = [](const float* p, int64_t ld) {
+    if (aligned(p, 16) && ld % 4 == 0) return 4;
+    if (aligned(p, 8) && ld % 2 == 0) return 2;
+    return 1;
+  };
+  const int vecA = vec_width(A, lda), vecB = vec_width(B, ldb);
   int rc;
 #define MGGCN_GEMM_ARGS opA, opB, s, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial, vecA, vecB, st
   if (s.bn == 128 && s.bk == 32) rc = launch_ops<128, 128, 32, 2, 2>(MGGCN_GEMM_ARGS);
