@@ -135,6 +135,15 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr /*d
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max);
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws /*dev*/, size_t ws_bytes, void* stream);
 int mggcn_graph_destroy(mggcn_graph* g);
+/* (Re)build the "sweep" form of the operator and use it for every SpMM on this graph: rows dealt
+ * to teams of rows_per_team rows (4, 8 or 16; 0 = default) with equal entry totals, each team's
+ * entries stored contiguously in (column panel, row, column) order over n_panels panels
+ * (0 = default), so that one launch sweeps all teams through the panels together and writes each
+ * row of Y once.  mggcn_graph_create builds it by itself for graphs with long rows and a large
+ * dense operand; this call forces it (tests, tuning).  Reads the CSR arrays back to the host,
+ * SYNCHRONISES, invalidates the binding: call mggcn_graph_bind afterwards.  Column count must
+ * fit 28 bits. */
+int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_team, void* stream);
 /* Number of column-panel passes a plain (epilogue NONE or RELU) SpMM of width F with the given
  * op makes on this graph (1 = single pass), or a negative status. */
 int mggcn_graph_panels(const mggcn_graph* g, int op /*mggcn_op*/, int32_t F);

@@ -91,7 +91,7 @@ class Graph:
     """Owns an mggcn_graph handle, keeps the CSR tensors and the bound workspace alive."""
 
     def __init__(self, n_rows, n_cols, rowptr, colidx, val, transpose=None, F_max=256, seg_len=0, n_panels=0,
-                 stream=None):
+                 sweep=None, stream=None):
         L = B.lib()
         self.n_rows, self.n_cols = n_rows, n_cols
         self._keep = [rowptr, colidx, val, transpose]
@@ -103,6 +103,8 @@ class Graph:
         self.device = rowptr.device
         self.ws = None
         self.F_max = 0
+        if sweep is not None:  # (n_panels, rows_per_team): force the sweep form
+            B.check(L.mggcn_graph_build_sweep(h, int(sweep[0]), int(sweep[1]), _stream(stream)))
         self.bind(F_max, stream)
 
     def bind(self, F_max, stream=None):

@@ -35,6 +35,7 @@ SIGNATURES = {
     "mggcn_graph_bind": (C.c_int, [_vp, _i32, _vp, _sz, _vp]),
     "mggcn_graph_destroy": (C.c_int, [_vp]),
     "mggcn_graph_panels": (C.c_int, [_vp, C.c_int, _i32]),
+    "mggcn_graph_build_sweep": (C.c_int, [_vp, _i32, _i32, _vp]),
     "mggcn_spmm": (C.c_int, [_vp, C.c_int, _vp, _i64, _i32, _f32, C.c_int, _vp, _i64, _vp]),
     "mggcn_gemm_workspace_bytes": (_sz, [C.c_int, C.c_int, _i64, _i64, _i64]),
     "mggcn_gemm": (C.c_int, [C.c_int, C.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _f32, C.c_int, _vp, _i64,

@@ -29,6 +29,7 @@
 //   1/n_chunks column slice of X instead of all of it.
 #include "common.h"
 #include "graph.h"
+#include "spmm_device.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -141,78 +142,6 @@ int32_t choose_panels(int32_t n_rows, int32_t n_cols, int64_t nnz) {
 // device code
 // ---------------------------------------------------------------------------------------
 
-template <int VW>
-__device__ inline void load_row(const float* __restrict__ p, int nf, float (&x)[VW]) {
-  if (nf == VW) {
-    if constexpr (VW == 4) {
-      const float4 t = *reinterpret_cast<const float4*>(p);
-      x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-    } else if constexpr (VW == 2) {
-      const float2 t = *reinterpret_cast<const float2*>(p);
-      x[0] = t.x; x[1] = t.y;
-    } else {
-      x[0] = p[0];
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < VW; ++i) x[i] = (i < nf) ? p[i] : 0.f;
-  }
-}
-
-__device__ inline float apply_epilogue(float acc, float old, float beta, int epi) {
-  if (beta != 0.f) acc += old;
-  if (epi == MGGCN_EPI_RELU) acc = acc > 0.f ? acc : 0.f;
-  if (epi == MGGCN_EPI_RELU_MASK) acc = old > 0.f ? acc : 0.f;
-  return acc;
-}
-
-template <int VW>
-__device__ inline void store_out(float* __restrict__ dst, int nf, const float (&a)[VW], float beta,
-                                 int epi, bool final_row) {
-  float r[VW];
-  if (final_row && (beta != 0.f || epi == MGGCN_EPI_RELU_MASK)) {
-    float old[VW];
-    load_row<VW>(dst, nf, old);
-#pragma unroll
-    for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(a[i], old[i], beta, epi);
-  } else if (final_row) {
-#pragma unroll
-    for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(a[i], 0.f, 0.f, epi);
-  } else {
-#pragma unroll
-    for (int i = 0; i < VW; ++i) r[i] = a[i];
-  }
-  if (nf == VW) {
-    if constexpr (VW == 4) {
-      *reinterpret_cast<float4*>(dst) = make_float4(r[0], r[1], r[2], r[3]);
-    } else if constexpr (VW == 2) {
-      *reinterpret_cast<float2*>(dst) = make_float2(r[0], r[1]);
-    } else {
-      dst[0] = r[0];
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < VW; ++i)
-      if (i < nf) dst[i] = r[i];
-  }
-}
-
-// Whole-vector load of VW floats.  The tail lane of a row may read up to VW-1 floats past F:
-// they lie inside the row's leading dimension (ld is a multiple of VW on this path) and only
-// feed accumulator components that are never stored.
-template <int VW>
-__device__ inline void load_vec(const float* __restrict__ p, float (&x)[VW]) {
-  if constexpr (VW == 4) {
-    const float4 t = *reinterpret_cast<const float4*>(p);
-    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
-  } else if constexpr (VW == 2) {
-    const float2 t = *reinterpret_cast<const float2*>(p);
-    x[0] = t.x; x[1] = t.y;
-  } else {
-    x[0] = p[0];
-  }
-}
-
 template <int VW, int LPR, int GPT, int UMAX>
 __global__ __launch_bounds__(kThreads) void spmm_tasks(
     const Task* __restrict__ tasks, int64_t ntasks, const int32_t* __restrict__ colidx,
@@ -270,6 +199,15 @@ __global__ __launch_bounds__(kThreads) void spmm_tasks(
     c = __builtin_nontemporal_load(cptr);
     v = __builtin_nontemporal_load(vptr);
   }
+  // what the output row holds now, if the epilogue needs it: fetched up front so that its
+  // latency hides behind the gathers
+  const float my_beta = (task.len_flags & kTaskFirst) ? beta : 1.f;
+  const int my_epi = (task.len_flags & kTaskLast) ? epi : (int)MGGCN_EPI_NONE;
+  const bool to_y = has_task && g == 0 && live && task.slot < 0;
+  float old[VW];
+#pragma unroll
+  for (int i = 0; i < VW; ++i) old[i] = 0.f;
+  if (to_y && (my_beta != 0.f || my_epi == MGGCN_EPI_RELU_MASK)) load_row<VW>(Y + (int64_t)task.row * ldy + f0, nf, old);
   for (int base = 0; base < maxlen; base += TEAM) {
     int c_next = 0;
     float v_next = 0.f;
@@ -324,9 +262,12 @@ __global__ __launch_bounds__(kThreads) void spmm_tasks(
   if (has_task && g == 0 && live) {
     if (task.slot >= 0)
       store_out<VW>(partial + (int64_t)task.slot * ldp + f0, nf, acc, 0.f, MGGCN_EPI_NONE, false);
-    else
-      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, acc, (task.len_flags & kTaskFirst) ? beta : 1.f,
-                    (task.len_flags & kTaskLast) ? epi : (int)MGGCN_EPI_NONE, true);
+    else {
+      float r[VW];
+#pragma unroll
+      for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(acc[i], old[i], my_beta, my_epi);
+      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, r, 0.f, MGGCN_EPI_NONE, false);
+    }
   }
 }
 
@@ -373,7 +314,8 @@ int launch_one(const LaunchArgs& a) {
   const int64_t blocks = ceil_div(a.ntasks, teams_per_block) * a.n_chunks;
   MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "SpMM grid of %lld blocks too large",
                 (long long)blocks);
-  spmm_tasks<VW, LPR, GPT, 8><<<(unsigned)blocks, kThreads, 0, a.stream>>>(
+  // 4 gathers per lane in flight: 56 VGPRs, 8 wavefronts per SIMD (8 in flight measured no faster)
+  spmm_tasks<VW, LPR, GPT, 4><<<(unsigned)blocks, kThreads, 0, a.stream>>>(
       a.tasks, a.ntasks, a.colidx, a.val, a.X, (uint32_t)(a.ldx * 4), a.F, a.n_chunks, a.beta, a.epi, a.Y,
       a.ldy, a.partial, a.ldp);
   MGGCN_LAUNCH_CHECK();
@@ -426,9 +368,17 @@ int pow2_ceil(int x) {
   return p;
 }
 
+struct SweepCarve {
+  uint32_t* scol;
+  float* sval;
+  int32_t *team_begin, *slot_row, *slot_out;
+  FixRow* fix;
+};
+
 struct GraphCarve {
   Task* tasks[2][2];   // [orientation][flat, panelled]
   FixRow* fix[2][2];
+  SweepCarve sweep[2];
   float* partial;
   int64_t ldp;
 };
@@ -447,11 +397,60 @@ size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* ou
       gc.fix[o][k] = c.take<FixRow>(sets[k]->fix.size() + 1);
       slots = std::max(slots, sets[k]->n_slots);
     }
+    const SweepSet& sw = os[o]->sweep;
+    if (sw.n_panels > 0) {
+      gc.sweep[o].scol = c.take<uint32_t>(sw.scol.size() + 64);  // slack: the stream prefetch reads ahead
+      gc.sweep[o].sval = c.take<float>(sw.sval.size() + 64);
+      gc.sweep[o].team_begin = c.take<int32_t>(sw.team_begin.size());
+      gc.sweep[o].slot_row = c.take<int32_t>(sw.slot_row.size());
+      gc.sweep[o].slot_out = c.take<int32_t>(sw.slot_out.size());
+      gc.sweep[o].fix = c.take<FixRow>(sw.fix.size() + 1);
+      slots = std::max(slots, sw.n_slots);
+    }
   }
   gc.ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
   gc.partial = c.take<float>((size_t)(slots * gc.ldp) + 64);
   if (out) *out = gc;
   return c.off;
+}
+
+// Sweep form is worth building when rows are long (the team streams stay long compared with the
+// per-row bookkeeping) and X is far larger than L2.
+bool sweep_pays(int32_t n_rows, int32_t n_cols, int64_t nnz) {
+  return n_rows > 0 && nnz / n_rows >= 64 && (int64_t)n_cols * 512 >= (24ll << 20) &&
+         (int64_t)n_cols <= (int64_t)kSweepColMask;
+}
+
+int32_t default_sweep_panels(int32_t n_cols) {
+  if (const char* e = std::getenv("MGGCN_SWEEP_PANELS")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 4096) return v;
+  }
+  // one panel of X at a reference width of 128 floats ~ 2 MB: a few panels fit one 4 MB L2
+  int64_t p = 1;
+  while (p * (2ll << 20) < (int64_t)n_cols * 512) p <<= 1;
+  return (int32_t)std::min<int64_t>(p, 1024);
+}
+
+int32_t default_sweep_rows() {
+  if (const char* e = std::getenv("MGGCN_SWEEP_R")) {
+    const int v = std::atoi(e);
+    if (v == 4 || v == 8 || v == 16) return v;
+  }
+  return 8;
+}
+
+int build_sweep_for(Orientation* o, int32_t n_panels, int32_t rows_per_team, hipStream_t s) {
+  std::vector<int32_t> rp((size_t)o->n_rows + 1), ci((size_t)o->nnz);
+  std::vector<float> va((size_t)o->nnz);
+  MGGCN_HIP(hipMemcpyAsync(rp.data(), o->rowptr, sizeof(int32_t) * rp.size(), hipMemcpyDeviceToHost, s));
+  if (o->nnz > 0) {
+    MGGCN_HIP(hipMemcpyAsync(ci.data(), o->colidx, sizeof(int32_t) * ci.size(), hipMemcpyDeviceToHost, s));
+    MGGCN_HIP(hipMemcpyAsync(va.data(), o->val, sizeof(float) * va.size(), hipMemcpyDeviceToHost, s));
+  }
+  MGGCN_HIP(hipStreamSynchronize(s));
+  build_sweep_set(&o->sweep, o->n_rows, o->n_cols, rp.data(), ci.data(), va.data(), n_panels, rows_per_team);
+  return MGGCN_OK;
 }
 
 }  // namespace
@@ -517,6 +516,10 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
       MGGCN_HIP(hipStreamSynchronize(s));
       build_task_set(&o->panelled, nr, nc, h, hc.data(), P, seg_len);
     }
+    // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
+    // and lose the shared panel), so it is built only on request.
+    if (n_panels == 0 && sweep_pays(nr, nc, o->nnz) && std::getenv("MGGCN_SWEEP"))
+      return build_sweep_for(o, default_sweep_panels(nc), default_sweep_rows(), s);
     return MGGCN_OK;
   };
   int rc = setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val);
@@ -562,6 +565,23 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
                                  hipMemcpyHostToDevice, s));
     }
   }
+  for (int o = 0; o < 2; ++o) {
+    if (!os[o] || os[o]->sweep.n_panels == 0) continue;
+    SweepSet& sw = os[o]->sweep;
+    sw.d_scol = gc.sweep[o].scol; sw.d_sval = gc.sweep[o].sval; sw.d_team_begin = gc.sweep[o].team_begin;
+    sw.d_slot_row = gc.sweep[o].slot_row; sw.d_slot_out = gc.sweep[o].slot_out; sw.d_fix = gc.sweep[o].fix;
+    auto up = [&](void* dst, const void* src, size_t bytes) -> int {
+      if (bytes) MGGCN_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
+      return MGGCN_OK;
+    };
+    int rc = up(sw.d_scol, sw.scol.data(), sizeof(uint32_t) * sw.scol.size());
+    if (!rc) rc = up(sw.d_sval, sw.sval.data(), sizeof(float) * sw.sval.size());
+    if (!rc) rc = up(sw.d_team_begin, sw.team_begin.data(), sizeof(int32_t) * sw.team_begin.size());
+    if (!rc) rc = up(sw.d_slot_row, sw.slot_row.data(), sizeof(int32_t) * sw.slot_row.size());
+    if (!rc) rc = up(sw.d_slot_out, sw.slot_out.data(), sizeof(int32_t) * sw.slot_out.size());
+    if (!rc) rc = up(sw.d_fix, sw.fix.data(), sizeof(FixRow) * sw.fix.size());
+    if (rc) return rc;
+  }
   MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
   g->d_partial = gc.partial;
   g->ldp = gc.ldp;
@@ -575,13 +595,33 @@ int mggcn_graph_destroy(mggcn_graph* g) {
   return MGGCN_OK;
 }
 
+int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_team, void* stream) {
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
+  MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 4096, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 4096]", n_panels);
+  MGGCN_REQUIRE(rows_per_team == 0 || rows_per_team == 4 || rows_per_team == 8 || rows_per_team == 16,
+                MGGCN_E_INVALID_ARG, "rows_per_team must be 0 (default), 4, 8 or 16");
+  MGGCN_REQUIRE((int64_t)g->fwd.n_cols <= (int64_t)kSweepColMask && (int64_t)g->fwd.n_rows <= (int64_t)kSweepColMask,
+                MGGCN_E_UNSUPPORTED, "sweep form holds column indices in 28 bits");
+  hipStream_t s = as_stream(stream);
+  Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
+  for (int o = 0; o < 2; ++o) {
+    if (!os[o]) continue;
+    const int rc = build_sweep_for(os[o], n_panels > 0 ? n_panels : default_sweep_panels(os[o]->n_cols),
+                                   rows_per_team > 0 ? rows_per_team : default_sweep_rows(), s);
+    if (rc) return rc;
+  }
+  g->sweep_forced = true;
+  g->bound = false;  // the tables changed: bind again
+  return MGGCN_OK;
+}
+
 int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
   MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
-  const bool use_panels = o.panelled.n_panels > 1 &&
-                          (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
-  return use_panels ? o.panelled.n_panels : 1;
+  const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
+  if (o.sweep.n_panels > 0 && (g->sweep_forced || big)) return 1;  // sweep form: one launch
+  return (o.panelled.n_panels > 1 && big) ? o.panelled.n_panels : 1;
 }
 
 int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_t F, float beta,
@@ -618,6 +658,22 @@ int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_
   const bool use_panels = o.panelled.n_panels > 1 && epilogue != MGGCN_EPI_RELU_MASK &&
                           (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
   const TaskSet& ts = use_panels ? o.panelled : o.flat;
+
+  // Sweep form (one launch, every row of Y written once) where it was built and X is large.
+  if (o.sweep.n_panels > 0 && vw == 4 && lpr >= 4 &&
+      (g->sweep_forced || (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes)) {
+    const SweepSet& sw = o.sweep;
+    const int rc = launch_sweep(sw, X, ldx, F, lpr, n_chunks, beta, epilogue, Y, ldy, g->d_partial, g->ldp, stream);
+    if (rc == MGGCN_OK) {
+      if (!sw.fix.empty()) {
+        spmm_fixup<<<(unsigned)sw.fix.size(), kThreads, 0, as_stream(stream)>>>(
+            sw.d_fix, (int64_t)sw.fix.size(), g->d_partial, g->ldp, F, beta, epilogue, Y, ldy);
+        MGGCN_LAUNCH_CHECK();
+      }
+      return MGGCN_OK;
+    }
+    if (rc != MGGCN_E_UNSUPPORTED) return rc;
+  }
 
   LaunchArgs a;
   a.colidx = o.colidx; a.val = o.val; a.X = X; a.ldx = ldx; a.F = F; a.n_chunks = n_chunks;

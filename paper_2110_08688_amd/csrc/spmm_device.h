@@ -1,0 +1,83 @@
+// Device helpers shared by the SpMM kernels: vector loads along the feature dimension and the
+// fused epilogue / masked store of an output row.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "../../include/mggcn.h"
+
+namespace mggcn {
+
+template <int VW>
+__device__ inline void load_row(const float* __restrict__ p, int nf, float (&x)[VW]) {
+  if (nf == VW) {
+    if constexpr (VW == 4) {
+      const float4 t = *reinterpret_cast<const float4*>(p);
+      x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    } else if constexpr (VW == 2) {
+      const float2 t = *reinterpret_cast<const float2*>(p);
+      x[0] = t.x; x[1] = t.y;
+    } else {
+      x[0] = p[0];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VW; ++i) x[i] = (i < nf) ? p[i] : 0.f;
+  }
+}
+
+__device__ inline float apply_epilogue(float acc, float old, float beta, int epi) {
+  if (beta != 0.f) acc += old;
+  if (epi == MGGCN_EPI_RELU) acc = acc > 0.f ? acc : 0.f;
+  if (epi == MGGCN_EPI_RELU_MASK) acc = old > 0.f ? acc : 0.f;
+  return acc;
+}
+
+template <int VW>
+__device__ inline void store_out(float* __restrict__ dst, int nf, const float (&a)[VW], float beta,
+                                 int epi, bool final_row) {
+  float r[VW];
+  if (final_row && (beta != 0.f || epi == MGGCN_EPI_RELU_MASK)) {
+    float old[VW];
+    load_row<VW>(dst, nf, old);
+#pragma unroll
+    for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(a[i], old[i], beta, epi);
+  } else if (final_row) {
+#pragma unroll
+    for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(a[i], 0.f, 0.f, epi);
+  } else {
+#pragma unroll
+    for (int i = 0; i < VW; ++i) r[i] = a[i];
+  }
+  if (nf == VW) {
+    if constexpr (VW == 4) {
+      *reinterpret_cast<float4*>(dst) = make_float4(r[0], r[1], r[2], r[3]);
+    } else if constexpr (VW == 2) {
+      *reinterpret_cast<float2*>(dst) = make_float2(r[0], r[1]);
+    } else {
+      dst[0] = r[0];
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < VW; ++i)
+      if (i < nf) dst[i] = r[i];
+  }
+}
+
+// Whole-vector load of VW floats.  The tail lane of a row may read up to VW-1 floats past F:
+// they lie inside the row's leading dimension (ld is a multiple of VW on this path) and only
+// feed accumulator components that are never stored.
+template <int VW>
+__device__ inline void load_vec(const float* __restrict__ p, float (&x)[VW]) {
+  if constexpr (VW == 4) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+  } else if constexpr (VW == 2) {
+    const float2 t = *reinterpret_cast<const float2*>(p);
+    x[0] = t.x; x[1] = t.y;
+  } else {
+    x[0] = p[0];
+  }
+}
+
+}  // namespace mggcn

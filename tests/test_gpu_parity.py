@@ -318,6 +318,60 @@ def test_spmm_column_panels(mg, dev, ref, spmm_graphs, name, P, seg):
         assert_rows_close(masked, np.where(Y0 > 0, want, 0.0), what=f"panels mask F={F}")
 
 
+@pytest.mark.parametrize("name", ["adversarial", "powerlaw", "rmat", "tiny"])
+@pytest.mark.parametrize("P,R", [(1, 8), (4, 4), (37, 8), (64, 16)])
+def test_spmm_sweep_form(mg, dev, ref, spmm_graphs, name, P, R):
+    """The sweep form (teams of R rows streaming their entries panel by panel, rows of Y held on
+    chip and written once) gives the same product, with beta and all three epilogues, cut hub
+    rows included."""
+    import torch
+
+    say(f"[spmm sweep] graph={name} P={P} R={R}")
+    g, rp, ci, val, _ = spmm_graphs[name]
+    n = g.n_rows
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=640, sweep=(P, R))
+    v64 = val.astype(np.float64)
+    for F, ld in ((16, 16), (41, 48), (128, 128), (256, 260), (602, 608)):
+        Xp = wl.normal_f32(77, F, (n, ld))
+        Y0 = wl.normal_f32(78, F, (n, ld))
+        Xd = to_dev(Xp, dev)
+        want = ref.spmm(ref.OP_N, n, n, rp, ci, v64, Xp[:, :F].astype(np.float64))
+        Yd = torch.full((n, ld), 7.0, device=dev)
+        mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], Y=Yd[:, :F])
+        got = Yd.cpu().numpy()
+        assert_rows_close(got[:, :F], want, what=f"sweep F={F}")
+        assert np.all(got[:, F:] == 7.0)
+        Y2 = torch.full((n, ld), 7.0, device=dev)
+        mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], Y=Y2[:, :F])
+        assert torch.equal(Yd, Y2), "sweep form must be reproducible"
+        Yr = torch.empty((n, ld), device=dev)
+        mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], epilogue=mg.EPI_RELU, Y=Yr[:, :F])
+        assert np.array_equal(Yr.cpu().numpy()[:, :F], np.maximum(got[:, :F], 0.0))
+        Ya = to_dev(Y0, dev)
+        mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], beta=1.0, Y=Ya[:, :F])
+        assert_rows_close(Ya.cpu().numpy()[:, :F], want + Y0[:, :F].astype(np.float64), what=f"sweep beta F={F}")
+        Ym = to_dev(Y0, dev)
+        mg.mggcn_spmm(G, mg.OP_N, Xd[:, :F], epilogue=mg.EPI_RELU_MASK, Y=Ym[:, :F])
+        assert np.array_equal(Ym.cpu().numpy()[:, :F], np.where(Y0[:, :F] > 0, got[:, :F], 0.0).astype(np.float32))
+
+
+def test_spmm_sweep_form_nonsymmetric(mg, dev, ref):
+    import scipy.sparse as sp
+
+    S = sp.random(1200, 1200, density=0.03, format="csr", random_state=9, dtype=np.float32)
+    S.setdiag(0); S.eliminate_zeros(); S.sort_indices()
+    rp, ci, val = ref.csr_normalize(1200, 1200, S.indptr.astype(np.int32), S.indices.astype(np.int32),
+                                    mode=ref.NORM_MEAN_IN)
+    v32 = val.astype(np.float32)
+    d = [to_dev(a, dev) for a in (rp, ci, v32)]
+    t = mg.mggcn_csr_transpose(1200, 1200, *d)
+    G = mg.Graph(1200, 1200, *d, transpose=t, F_max=64, sweep=(8, 8))
+    X = wl.normal_f32(5, 5, (1200, 48))
+    for op, rop in ((mg.OP_N, ref.OP_N), (mg.OP_T, ref.OP_T)):
+        want = ref.spmm(rop, 1200, 1200, rp, ci, v32.astype(np.float64), X.astype(np.float64))
+        assert_rows_close(mg.mggcn_spmm(G, op, to_dev(X, dev)).cpu().numpy(), want, what=f"sweep op={op}")
+
+
 # ----------------------------------------------------------------------------------------------
 # a1 / a7 / a8: GeMM
 # ----------------------------------------------------------------------------------------------
