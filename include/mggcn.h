@@ -201,10 +201,24 @@ int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits /*dev*/, int64_t 
  * ---------------------------------------------------------------------------------------- */
 typedef struct mggcn_model mggcn_model;
 
+/* Model flags.
+ * MGGCN_MODEL_CACHE_INPUT: the input features X do not change between epochs, so A^ X is formed
+ * once (mggcn_model_cache_input) and kept in the arena; the first layer then runs as
+ * relu((A^ X) W) forward and W_G = (A^ X)^T Z_G backward with no SpMM at all in either pass --
+ * the exact form of the paper's "saving one SpMM" (section "Order of Computation and Saving one
+ * SpMM").  Costs one n x d_0 buffer. */
+enum { MGGCN_MODEL_CACHE_INPUT = 1 };
+
 int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims /*host*/,
-                       const int32_t* orders /*host or NULL*/, mggcn_model** out);
+                       const int32_t* orders /*host or NULL*/, int32_t flags, mggcn_model** out);
 int mggcn_model_destroy(mggcn_model* m);
-int32_t mggcn_model_spmm_width_max(const int32_t* dims /*host*/, const int32_t* orders, int32_t L);
+int32_t mggcn_model_spmm_width_max(const int32_t* dims /*host*/, const int32_t* orders, int32_t L,
+                                   int32_t flags);
+/* With MGGCN_MODEL_CACHE_INPUT: compute and keep A^ X (one SpMM of width d_0).  Call after
+ * mggcn_model_bind and again whenever X changes; mggcn_epoch / mggcn_layer_fwd(l = 0) fail with
+ * MGGCN_E_INVALID_ARG until it has been called, and afterwards ignore their X / H_in argument
+ * for the first layer. */
+int mggcn_model_cache_input(mggcn_model* m, const float* X /*dev*/, int64_t ldx, void* stream);
 size_t mggcn_model_arena_bytes(const mggcn_model* m);
 int mggcn_model_bind(mggcn_model* m, void* arena /*dev*/, size_t arena_bytes);
 /* resolved order of layer l (mggcn_order), or a negative status */
@@ -215,7 +229,8 @@ int mggcn_model_activation(const mggcn_model* m, int32_t l, float** ptr_out, int
 
 /* One layer forward (Eq. 5-7): H_out = [relu]( A^ H_in W ).  H_in is n x d_l, W is
  * d_l x d_{l+1}, H_out is n x d_{l+1}; relu != 0 applies Eq. 7.  Uses the model's shared
- * temporary (and, SpMM-first, stores A^ H_in in the layer's own buffer). */
+ * temporary (and, SpMM-first, stores A^ H_in in the layer's own buffer).  With
+ * MGGCN_MODEL_CACHE_INPUT, l = 0 ignores H_in (may be NULL) and works from the stored A^ X. */
 int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in, const float* W,
                     int64_t ldw, int relu, float* H_out, int64_t ld_out, void* stream);
 
@@ -237,7 +252,8 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
  * X: n x d_0 (ld ldx).  labels: n int32.  W / W_G: host arrays of L device pointers, W[l]
  * and W_G[l] dense d_l x d_{l+1} (ld = d_{l+1}).  loss_dev: one fp32 on the device.  No
  * gradient with respect to X is formed; the first layer's backward SpMM is kept whenever
- * W_G needs it (GeMM-first order) and absent otherwise. */
+ * W_G needs it (GeMM-first order) and absent otherwise.  With MGGCN_MODEL_CACHE_INPUT, X is
+ * ignored (may be NULL): the first layer works from the stored A^ X. */
 int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labels,
                 const float* const* W /*host array of dev ptrs*/, float* loss_dev,
                 float* const* W_G /*host array of dev ptrs*/, void* stream);

@@ -12,7 +12,7 @@ import ctypes as C
 from . import binding as B
 from .binding import (  # noqa: F401  (re-exported constants)
     EPI_NONE, EPI_RELU, EPI_RELU_MASK, NORM_MEAN_IN, NORM_SYM_SELFLOOP, OP_N, OP_T, ORDER_AUTO,
-    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MggcnError,
+    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MODEL_CACHE_INPUT, MggcnError,
 )
 
 
@@ -189,27 +189,27 @@ def mggcn_softmax_ce(logits, labels, dlogits=None, stream=None):
 # model: layers and epoch
 # ------------------------------------------------------------------------------------------
 
-def mggcn_model_spmm_width_max(dims, orders=None) -> int:
+def mggcn_model_spmm_width_max(dims, orders=None, flags=0) -> int:
     L = len(dims) - 1
     d = (C.c_int32 * (L + 1))(*dims)
     o = (C.c_int32 * L)(*orders) if orders is not None else None
-    return B.lib().mggcn_model_spmm_width_max(d, o, L)
+    return B.lib().mggcn_model_spmm_width_max(d, o, L, flags)
 
 
 class Model:
     """Owns an mggcn_model handle and its activation arena (a device tensor)."""
 
-    def __init__(self, graph: Graph, dims, orders=None):
+    def __init__(self, graph: Graph, dims, orders=None, flags=0):
         L = B.lib()
         self.graph, self.dims = graph, list(dims)
         self.L = len(dims) - 1
-        need = mggcn_model_spmm_width_max(dims, orders)
+        need = mggcn_model_spmm_width_max(dims, orders, flags)
         if graph.F_max < need:
             graph.bind(need)
         d = (C.c_int32 * (self.L + 1))(*dims)
         o = (C.c_int32 * self.L)(*orders) if orders is not None else None
         h = C.c_void_p(None)
-        B.check(L.mggcn_model_create(graph.handle, self.L, d, o, C.byref(h)))
+        B.check(L.mggcn_model_create(graph.handle, self.L, d, o, flags, C.byref(h)))
         self.handle = h
         nbytes = L.mggcn_model_arena_bytes(h)
         self.arena = _ws(nbytes, graph.device)
@@ -217,6 +217,10 @@ class Model:
 
     def order(self, l) -> int:
         return B.check(B.lib().mggcn_model_order(self.handle, l))
+
+    def cache_input(self, X, stream=None):
+        """MODEL_CACHE_INPUT: form and keep A^ X (call once, and again whenever X changes)."""
+        B.check(B.lib().mggcn_model_cache_input(self.handle, B.ptr(X), B.ld_of(X), _stream(stream)))
 
     def activation(self, l):
         """(device address, ld) of layer l's result buffer"""
@@ -278,9 +282,9 @@ def mggcn_epoch(model: Model, X, labels, Ws, W_Gs=None, loss=None, stream=None):
     if W_Gs is None:
         W_Gs = [torch.empty_like(w) for w in Ws]
     if loss is None:
-        loss = torch.empty(1, dtype=torch.float32, device=X.device)
+        loss = torch.empty(1, dtype=torch.float32, device=labels.device)
     Wp = (C.c_void_p * model.L)(*[w.data_ptr() for w in Ws])
     Gp = (C.c_void_p * model.L)(*[w.data_ptr() for w in W_Gs])
-    B.check(B.lib().mggcn_epoch(model.handle, B.ptr(X), B.ld_of(X), B.ptr(labels), Wp, B.ptr(loss), Gp,
-                                _stream(stream)))
+    B.check(B.lib().mggcn_epoch(model.handle, B.ptr(X), B.ld_of(X) if X is not None else 0, B.ptr(labels), Wp,
+                                B.ptr(loss), Gp, _stream(stream)))
     return loss, W_Gs

@@ -18,6 +18,7 @@ NORM_SYM_SELFLOOP, NORM_MEAN_IN = 0, 1
 OP_N, OP_T = 0, 1
 EPI_NONE, EPI_RELU, EPI_RELU_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = -1, 0, 1
+MODEL_CACHE_INPUT = 1
 
 _vp, _i32, _i64, _sz, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
 
@@ -43,9 +44,10 @@ SIGNATURES = {
     "mggcn_relu_bwd": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),
     "mggcn_softmax_ce_workspace_bytes": (_sz, [_i64]),
     "mggcn_softmax_ce": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
-    "mggcn_model_create": (C.c_int, [_vp, _i32, _vp, _vp, C.POINTER(_vp)]),
+    "mggcn_model_create": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(_vp)]),
+    "mggcn_model_cache_input": (C.c_int, [_vp, _vp, _i64, _vp]),
     "mggcn_model_destroy": (C.c_int, [_vp]),
-    "mggcn_model_spmm_width_max": (_i32, [_vp, _vp, _i32]),
+    "mggcn_model_spmm_width_max": (_i32, [_vp, _vp, _i32, _i32]),
     "mggcn_model_arena_bytes": (_sz, [_vp]),
     "mggcn_model_bind": (C.c_int, [_vp, _vp, _sz]),
     "mggcn_model_order": (C.c_int, [_vp, _i32]),

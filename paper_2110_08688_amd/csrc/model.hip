@@ -26,6 +26,8 @@ struct mggcn_model {
   size_t off_tmp = 0, off_gemm_ws = 0, off_loss_ws = 0;
   size_t gemm_ws_bytes = 0, loss_ws_bytes = 0, arena_bytes = 0;
   char* arena = nullptr;
+  bool cache_input = false;  // layer 0 works from a stored A^ X
+  bool cache_valid = false;
 };
 
 namespace mggcn {
@@ -52,22 +54,24 @@ using namespace mggcn;
 
 extern "C" {
 
-int32_t mggcn_model_spmm_width_max(const int32_t* dims, const int32_t* orders, int32_t L) {
+int32_t mggcn_model_spmm_width_max(const int32_t* dims, const int32_t* orders, int32_t L, int32_t flags) {
   if (!dims || L < 1) return 0;
   int32_t w = 0;
   for (int32_t l = 0; l < L; ++l) {
-    const int o = resolve_order(dims[l], dims[l + 1], orders ? orders[l] : MGGCN_ORDER_AUTO);
+    int o = resolve_order(dims[l], dims[l + 1], orders ? orders[l] : MGGCN_ORDER_AUTO);
+    if (l == 0 && (flags & MGGCN_MODEL_CACHE_INPUT)) o = MGGCN_ORDER_SPMM_FIRST;
     w = std::max(w, o == MGGCN_ORDER_SPMM_FIRST ? dims[l] : dims[l + 1]);
   }
   return w;
 }
 
 int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, const int32_t* orders,
-                       mggcn_model** out) {
+                       int32_t flags, mggcn_model** out) {
   MGGCN_REQUIRE(out != nullptr, MGGCN_E_INVALID_ARG, "out is NULL");
   *out = nullptr;
   MGGCN_REQUIRE(g != nullptr && dims != nullptr, MGGCN_E_INVALID_ARG, "graph / dims is NULL");
   MGGCN_REQUIRE(L >= 1 && L <= 64, MGGCN_E_INVALID_ARG, "layer count %d outside [1, 64]", L);
+  MGGCN_REQUIRE((flags & ~MGGCN_MODEL_CACHE_INPUT) == 0, MGGCN_E_INVALID_ARG, "unknown model flags 0x%x", flags);
   MGGCN_REQUIRE(g->fwd.n_rows == g->fwd.n_cols, MGGCN_E_INVALID_ARG,
                 "a model needs a square graph, got %d x %d", g->fwd.n_rows, g->fwd.n_cols);
   for (int32_t l = 0; l <= L; ++l)
@@ -81,6 +85,7 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   m->g = g;
   m->n = g->fwd.n_rows;
   m->L = L;
+  m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
   m->dims.assign(dims, dims + L + 1);
   m->orders.resize(L);
   m->ld_act.resize(L);
@@ -92,6 +97,7 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   int32_t tmp_width = 1;
   for (int32_t l = 0; l < L; ++l) {
     m->orders[l] = resolve_order(dims[l], dims[l + 1], orders ? orders[l] : MGGCN_ORDER_AUTO);
+    if (l == 0 && m->cache_input) m->orders[l] = MGGCN_ORDER_SPMM_FIRST;  // its A^ H buffer is the cache
     m->ld_act[l] = padded_ld(dims[l + 1]);
     m->off_act[l] = off;
     off += align_up(n * (size_t)m->ld_act[l] * sizeof(float), kWsAlign);
@@ -99,7 +105,7 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
       m->ld_p[l] = padded_ld(dims[l]);
       m->off_p[l] = off;
       off += align_up(n * (size_t)m->ld_p[l] * sizeof(float), kWsAlign);
-      tmp_width = std::max(tmp_width, dims[l]);
+      if (!(l == 0 && m->cache_input)) tmp_width = std::max(tmp_width, dims[l]);
     } else {
       tmp_width = std::max(tmp_width, dims[l + 1]);
     }
@@ -131,6 +137,19 @@ int mggcn_model_bind(mggcn_model* m, void* arena, size_t arena_bytes) {
   MGGCN_REQUIRE(arena_bytes >= m->arena_bytes, MGGCN_E_WORKSPACE, "arena too small: %zu bytes given, %zu needed",
                 arena_bytes, m->arena_bytes);
   m->arena = static_cast<char*>(arena);
+  m->cache_valid = false;
+  return MGGCN_OK;
+}
+
+int mggcn_model_cache_input(mggcn_model* m, const float* X, int64_t ldx, void* stream) {
+  MGGCN_REQUIRE(m != nullptr, MGGCN_E_INVALID_ARG, "model is NULL");
+  MGGCN_REQUIRE(m->cache_input, MGGCN_E_INVALID_ARG, "model was created without MGGCN_MODEL_CACHE_INPUT");
+  MGGCN_REQUIRE(m->arena != nullptr, MGGCN_E_WORKSPACE, "model is not bound to an arena");
+  MGGCN_REQUIRE(X != nullptr && ldx >= m->dims[0], MGGCN_E_INVALID_ARG, "X is NULL or ldx < d_0");
+  float* P = reinterpret_cast<float*>(m->arena + m->off_p[0]);
+  const int rc = mggcn_spmm(m->g, MGGCN_OP_N, X, ldx, m->dims[0], 0.f, MGGCN_EPI_NONE, P, m->ld_p[0], stream);
+  if (rc) return rc;
+  m->cache_valid = true;
   return MGGCN_OK;
 }
 
@@ -154,8 +173,11 @@ int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   int rc = check_layer(m, l);
   if (rc) return rc;
   const int32_t d_in = m->dims[l], d_out = m->dims[l + 1];
-  MGGCN_REQUIRE(H_in && W && H_out, MGGCN_E_INVALID_ARG, "H_in / W / H_out is NULL");
-  MGGCN_REQUIRE(ld_in >= d_in && ldw >= d_out && ld_out >= d_out, MGGCN_E_INVALID_ARG,
+  const bool cached = l == 0 && m->cache_input;
+  MGGCN_REQUIRE(!cached || m->cache_valid, MGGCN_E_INVALID_ARG,
+                "mggcn_model_cache_input has not been called since the model was bound");
+  MGGCN_REQUIRE((cached || H_in) && W && H_out, MGGCN_E_INVALID_ARG, "H_in / W / H_out is NULL");
+  MGGCN_REQUIRE((cached || ld_in >= d_in) && ldw >= d_out && ld_out >= d_out, MGGCN_E_INVALID_ARG,
                 "leading dimension too small for layer %d (%d -> %d)", l, d_in, d_out);
   const int epi = relu ? MGGCN_EPI_RELU : MGGCN_EPI_NONE;
   float* tmp = reinterpret_cast<float*>(m->arena + m->off_tmp);
@@ -169,8 +191,10 @@ int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   }
   // associativity:  P = A^ H ;  H' = relu(P W)
   float* P = reinterpret_cast<float*>(m->arena + m->off_p[l]);
-  rc = mggcn_spmm(m->g, MGGCN_OP_N, H_in, ld_in, d_in, 0.f, MGGCN_EPI_NONE, P, m->ld_p[l], stream);
-  if (rc) return rc;
+  if (!cached) {
+    rc = mggcn_spmm(m->g, MGGCN_OP_N, H_in, ld_in, d_in, 0.f, MGGCN_EPI_NONE, P, m->ld_p[l], stream);
+    if (rc) return rc;
+  }
   return mggcn_gemm(MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, P, m->ld_p[l], W, ldw, 0.f, epi, H_out, ld_out,
                     nullptr, 0, stream);
 }
@@ -181,12 +205,15 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   int rc = check_layer(m, l);
   if (rc) return rc;
   const int32_t d_in = m->dims[l], d_out = m->dims[l + 1];
-  MGGCN_REQUIRE(H_in && G && W && W_G, MGGCN_E_INVALID_ARG, "H_in / G / W / W_G is NULL");
-  MGGCN_REQUIRE(ld_in >= d_in && ldg >= d_out && ldw >= d_out && ldwg >= d_out, MGGCN_E_INVALID_ARG,
+  const bool cached = l == 0 && m->cache_input;
+  MGGCN_REQUIRE(!cached || m->cache_valid, MGGCN_E_INVALID_ARG,
+                "mggcn_model_cache_input has not been called since the model was bound");
+  MGGCN_REQUIRE((cached || H_in) && G && W && W_G, MGGCN_E_INVALID_ARG, "H_in / G / W / W_G is NULL");
+  MGGCN_REQUIRE((cached || ld_in >= d_in) && ldg >= d_out && ldw >= d_out && ldwg >= d_out, MGGCN_E_INVALID_ARG,
                 "leading dimension too small for layer %d (%d -> %d)", l, d_in, d_out);
   MGGCN_REQUIRE(!act || ld_act >= d_out, MGGCN_E_INVALID_ARG, "ld_act < %d", d_out);
   MGGCN_REQUIRE(!H_G || ldhg >= d_in, MGGCN_E_INVALID_ARG, "ldhg < %d", d_in);
-  MGGCN_REQUIRE(hg_relu_mask || H_G == nullptr || H_G != H_in, MGGCN_E_INVALID_ARG,
+  MGGCN_REQUIRE(hg_relu_mask || H_G == nullptr || H_in == nullptr || H_G != H_in, MGGCN_E_INVALID_ARG,
                 "H_G may alias H_in only with hg_relu_mask set");
   if (act) {  // Eq. 8, unfused
     rc = mggcn_relu_bwd(m->n, d_out, act, ld_act, G, ldg, stream);
@@ -222,8 +249,9 @@ int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labe
                 float* loss_dev, float* const* W_G, void* stream) {
   MGGCN_REQUIRE(m != nullptr, MGGCN_E_INVALID_ARG, "model is NULL");
   MGGCN_REQUIRE(m->arena != nullptr, MGGCN_E_WORKSPACE, "model is not bound to an arena");
-  MGGCN_REQUIRE(X && labels && W && loss_dev && W_G, MGGCN_E_INVALID_ARG, "NULL argument");
-  MGGCN_REQUIRE(ldx >= m->dims[0], MGGCN_E_INVALID_ARG, "ldx %lld < d_0 %d", (long long)ldx, m->dims[0]);
+  MGGCN_REQUIRE((X || m->cache_input) && labels && W && loss_dev && W_G, MGGCN_E_INVALID_ARG, "NULL argument");
+  MGGCN_REQUIRE(m->cache_input || ldx >= m->dims[0], MGGCN_E_INVALID_ARG, "ldx %lld < d_0 %d", (long long)ldx,
+                m->dims[0]);
   for (int32_t l = 0; l < m->L; ++l)
     MGGCN_REQUIRE(W[l] && W_G[l], MGGCN_E_INVALID_ARG, "W[%d] / W_G[%d] is NULL", l, l);
   const int32_t L = m->L;

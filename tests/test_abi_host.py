@@ -87,7 +87,8 @@ def test_argument_errors_need_no_device(B):
     assert L.mggcn_relu_bwd(4, 4, 256, 2, 256, 4, None) == B.E_INVALID_ARG
     # model
     dims = (C.c_int32 * 3)(602, 128, 41)
-    assert L.mggcn_model_create(None, 2, dims, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_model_create(None, 2, dims, None, 0, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_model_cache_input(None, 256, 4, None) == B.E_INVALID_ARG
     assert L.mggcn_epoch(None, 256, 4, 256, None, 256, None, None) == B.E_INVALID_ARG
     assert L.mggcn_layer_fwd(None, 0, 256, 4, 256, 4, 1, 256, 4, None) == B.E_INVALID_ARG
 
@@ -96,16 +97,17 @@ def test_spmm_width_rule(B):
     """SpMM runs at min(d_l, d_{l+1}): SpMM first iff d_l < d_{l+1}, tie -> GeMM first."""
     L = B.lib()
 
-    def width(dims, orders=None):
+    def width(dims, orders=None, flags=0):
         d = (C.c_int32 * len(dims))(*dims)
         o = (C.c_int32 * (len(dims) - 1))(*orders) if orders else None
-        return L.mggcn_model_spmm_width_max(d, o, len(dims) - 1)
+        return L.mggcn_model_spmm_width_max(d, o, len(dims) - 1, flags)
 
     assert width((602, 128, 41)) == 128
     assert width((100, 256, 256, 47)) == 256  # layer 2 is a tie -> GeMM first at width 256
     assert width((128, 256)) == 128
     assert width((128, 256), [B.ORDER_GEMM_FIRST]) == 256
     assert width((64, 16, 8)) == 16
+    assert width((602, 128, 41), flags=B.MODEL_CACHE_INPUT) == 602  # the one-off A^ X product
 
 
 def test_product_does_not_import_the_oracle():

@@ -550,3 +550,29 @@ def test_epoch(mg, dev, ref, cfg_name, dims, orders):
         # the order rule
         want_order = mg.ORDER_SPMM_FIRST if (ords is not None or dims[l] < dims[l + 1]) else mg.ORDER_GEMM_FIRST
         assert model.order(l) == want_order
+
+
+def test_epoch_with_cached_input(mg, dev, ref):
+    """MGGCN_MODEL_CACHE_INPUT: A^ X formed once, first layer without any SpMM in either pass;
+    the same gradients as the oracle evaluating that layer in the (A^ X) W association."""
+    g = wl.chung_lu(4000, 200e3, 2.1, 1500.0, 21)
+    dims = (50, 24, 7)
+    n = g.n_rows
+    rp, ci, val, X, Ws, labels = _model_inputs(ref, g, dims, 11)
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=64)
+    model = mg.Model(G, dims, flags=mg.MODEL_CACHE_INPUT)
+    assert model.order(0) == mg.ORDER_SPMM_FIRST and model.order(1) == mg.ORDER_GEMM_FIRST
+    Xd, Wd, ld = to_dev(X, dev), [to_dev(w, dev) for w in Ws], to_dev(labels, dev)
+    with pytest.raises(mg.MggcnError):
+        mg.mggcn_epoch(model, None, ld, Wd)  # cache not filled yet
+    model.cache_input(Xd)
+    loss, WG = mg.mggcn_epoch(model, None, ld, Wd)
+    loss2, WG2 = mg.mggcn_epoch(model, None, ld, Wd)  # the cache survives an epoch
+    masks = gpu_relu_decisions(mg, model, Xd, Wd)
+    rl, rWG, _ = ref.epoch(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
+                           [w.astype(np.float64) for w in Ws], orders=[ref.SPMM_FIRST, ref.GEMM_FIRST],
+                           relu_masks=masks)
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl) and loss.item() == loss2.item()
+    for l in range(2):
+        assert np.array_equal(WG[l].cpu().numpy(), WG2[l].cpu().numpy())
+        assert_rows_close(WG[l].cpu().numpy(), rWG[l], what=f"cached W_G[{l}]")
