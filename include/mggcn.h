@@ -188,6 +188,15 @@ int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits /*dev*/, int64_t 
                      const int32_t* labels /*dev*/, float* loss_dev, float* dlogits /*dev*/,
                      int64_t ldd, void* ws, size_t ws_bytes, void* stream);
 
+/* Adam update of one dense parameter array (the optimiser the paper trains with; it states no
+ * hyper-parameters, so they are arguments).  step counts from 1.  All arrays dev, `count` fp32
+ * elements, updated in place:
+ *   m <- beta1 m + (1-beta1) g ;  v <- beta2 v + (1-beta2) g^2
+ *   W <- W - lr (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps)
+ * Not part of mggcn_epoch (the benchmarked epoch is forward + backward). */
+int mggcn_adam_step(int64_t count, float* W, const float* G, float* m, float* v, int32_t step, float lr,
+                    float beta1, float beta2, float eps, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Model handle: L GCN layers H^(l+1) = relu( A^ H^(l) W^(l) ) (no ReLU after the last layer,
  * whose output are the logits), the per-layer order decision and the activation buffer plan

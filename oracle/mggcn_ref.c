@@ -401,3 +401,21 @@ int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const d
   free(H);
   return rc;
 }
+
+/* ------------------------------------------------------------------------
+ * Adam update (the optimiser the paper trains with; it states no hyper-parameters, so they are
+ * arguments).  Textbook form with bias correction, t = 1, 2, ...:
+ *   m <- b1 m + (1-b1) g ;  v <- b2 v + (1-b2) g^2
+ *   W <- W - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+ * --------------------------------------------------------------------- */
+int mggcn_ref_adam_step(int64_t count, double* W, const double* G, double* m, double* v, int t, double lr,
+                        double b1, double b2, double eps) {
+  if (count < 0 || t < 1) return REF_E_ARG;
+  const double c1 = 1.0 - pow(b1, (double)t), c2 = 1.0 - pow(b2, (double)t);
+  for (int64_t i = 0; i < count; ++i) {
+    m[i] = b1 * m[i] + (1.0 - b1) * G[i];
+    v[i] = b2 * v[i] + (1.0 - b2) * G[i] * G[i];
+    W[i] -= lr * (m[i] / c1) / (sqrt(v[i] / c2) + eps);
+  }
+  return REF_OK;
+}

@@ -63,6 +63,8 @@ def _load():
         ]
         lib.mggcn_ref_epoch.restype = i32
         lib.mggcn_ref_epoch.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+        lib.mggcn_ref_adam_step.restype = i32
+        lib.mggcn_ref_adam_step.argtypes = [i64, vp, vp, vp, vp, i32, dbl, dbl, dbl, dbl]
         _lib = lib
     return _lib
 
@@ -261,3 +263,13 @@ def epoch(n, rowptr, colidx, val, X, labels, Ws, orders=None, want_logits=False,
         "epoch",
     )
     return loss.value, WG, logits
+
+
+def adam_step(W, G, m, v, t, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8):
+    """In-place Adam update of float64 arrays W, m, v (all contiguous, same size as G)."""
+    for a in (W, m, v):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    G = _f64(G)
+    _check(_load().mggcn_ref_adam_step(W.size, W.ctypes.data, G.ctypes.data, m.ctypes.data, v.ctypes.data,
+                                        int(t), lr, b1, b2, eps), "adam_step")
+    return W, m, v

@@ -185,6 +185,14 @@ def mggcn_softmax_ce(logits, labels, dlogits=None, stream=None):
     return loss, dlogits
 
 
+def mggcn_adam_step(W, G, m, v, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
+    """In-place Adam update of a contiguous parameter tensor W with moments m, v."""
+    assert W.is_contiguous() and G.is_contiguous() and m.is_contiguous() and v.is_contiguous()
+    B.check(B.lib().mggcn_adam_step(W.numel(), B.ptr(W), B.ptr(G), B.ptr(m), B.ptr(v), int(step), lr, beta1, beta2,
+                                    eps, _stream(stream)))
+    return W
+
+
 # ------------------------------------------------------------------------------------------
 # model: layers and epoch
 # ------------------------------------------------------------------------------------------

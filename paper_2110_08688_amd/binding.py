@@ -42,6 +42,7 @@ SIGNATURES = {
     "mggcn_gemm": (C.c_int, [C.c_int, C.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _f32, C.c_int, _vp, _i64,
                              _vp, _sz, _vp]),
     "mggcn_relu_bwd": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),
+    "mggcn_adam_step": (C.c_int, [_i64, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _f32, _f32, _vp]),
     "mggcn_softmax_ce_workspace_bytes": (_sz, [_i64]),
     "mggcn_softmax_ce": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
     "mggcn_model_create": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(_vp)]),

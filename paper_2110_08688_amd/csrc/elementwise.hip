@@ -2,6 +2,8 @@
 // fused epilogues, and the softmax cross-entropy loss with its gradient.
 #include "common.h"
 
+#include <cmath>
+
 namespace mggcn {
 namespace {
 
@@ -86,6 +88,20 @@ __global__ __launch_bounds__(kThreads) void loss_finish(int64_t nblocks,
   if (threadIdx.x == 0) *loss = (float)(part[0] * inv_n);
 }
 
+__global__ __launch_bounds__(kThreads) void adam_kernel(int64_t count, float* __restrict__ W,
+                                                         const float* __restrict__ G, float* __restrict__ m,
+                                                         float* __restrict__ v, float lr, float b1, float b2,
+                                                         float eps, float inv_c1, float inv_c2) {
+  const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= count) return;
+  const float g = G[i];
+  const float mi = b1 * m[i] + (1.f - b1) * g;
+  const float vi = b2 * v[i] + (1.f - b2) * g * g;
+  m[i] = mi;
+  v[i] = vi;
+  W[i] -= lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
+}
+
 int team_lanes(int C) {
   int t = 1;
   while (t < C && t < 64) t <<= 1;
@@ -113,6 +129,24 @@ int mggcn_relu_bwd(int64_t rows, int32_t cols, const float* act, int64_t lda, fl
   const int64_t blocks = ceil_div(rows * cols, kThreads);
   MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "matrix too large for one launch");
   relu_bwd_kernel<<<(unsigned)blocks, kThreads, 0, as_stream(stream)>>>(rows, cols, act, lda, G, ldg);
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
+int mggcn_adam_step(int64_t count, float* W, const float* G, float* m, float* v, int32_t step, float lr,
+                    float beta1, float beta2, float eps, void* stream) {
+  MGGCN_REQUIRE(count >= 0, MGGCN_E_INVALID_ARG, "negative count %lld", (long long)count);
+  MGGCN_REQUIRE(step >= 1, MGGCN_E_INVALID_ARG, "step %d must start at 1", step);
+  MGGCN_REQUIRE(beta1 >= 0.f && beta1 < 1.f && beta2 >= 0.f && beta2 < 1.f, MGGCN_E_INVALID_ARG,
+                "beta1 / beta2 must lie in [0, 1)");
+  if (count == 0) return MGGCN_OK;
+  MGGCN_REQUIRE(W && G && m && v, MGGCN_E_INVALID_ARG, "NULL argument");
+  const int64_t blocks = ceil_div(count, kThreads);
+  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "too many parameters for one launch");
+  // bias corrections evaluated once on the host in double
+  const double c1 = 1.0 - pow((double)beta1, (double)step), c2 = 1.0 - pow((double)beta2, (double)step);
+  adam_kernel<<<(unsigned)blocks, kThreads, 0, as_stream(stream)>>>(count, W, G, m, v, lr, beta1, beta2, eps,
+                                                                   (float)(1.0 / c1), (float)(1.0 / c2));
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
 }

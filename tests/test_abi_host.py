@@ -85,6 +85,8 @@ def test_argument_errors_need_no_device(B):
     assert L.mggcn_softmax_ce(8, 4, 256, 3, 256, 256, 256, 4, 256, 1024, None) == B.E_INVALID_ARG
     assert L.mggcn_softmax_ce(8, 4, 256, 4, 256, 256, 256, 4, None, 0, None) == B.E_WORKSPACE
     assert L.mggcn_relu_bwd(4, 4, 256, 2, 256, 4, None) == B.E_INVALID_ARG
+    assert L.mggcn_adam_step(8, 256, 256, 256, 256, 0, 0.01, 0.9, 0.999, 1e-8, None) == B.E_INVALID_ARG
+    assert L.mggcn_adam_step(8, 256, 256, 256, 256, 1, 0.01, 1.0, 0.999, 1e-8, None) == B.E_INVALID_ARG
     # model
     dims = (C.c_int32 * 3)(602, 128, 41)
     assert L.mggcn_model_create(None, 2, dims, None, 0, C.byref(h)) == B.E_INVALID_ARG

@@ -576,3 +576,20 @@ def test_epoch_with_cached_input(mg, dev, ref):
     for l in range(2):
         assert np.array_equal(WG[l].cpu().numpy(), WG2[l].cpu().numpy())
         assert_rows_close(WG[l].cpu().numpy(), rWG[l], what=f"cached W_G[{l}]")
+
+
+def test_adam_step(mg, dev, ref):
+    import torch
+
+    W0 = wl.normal_f32(3, 60, (602, 128))
+    W = W0.astype(np.float64).copy()
+    m, v = np.zeros_like(W), np.zeros_like(W)
+    Wd = to_dev(W0, dev)
+    md, vd = torch.zeros_like(Wd), torch.zeros_like(Wd)
+    for t in range(1, 6):
+        g = wl.normal_f32(3, 60 + t, (602, 128)) * 10.0 ** (t - 4)
+        ref.adam_step(W, g.astype(np.float64), m, v, t, lr=0.01)
+        mg.mggcn_adam_step(Wd, to_dev(g, dev), md, vd, t, lr=0.01)
+        assert_rows_close(Wd.cpu().numpy(), W, tol=1e-5, what=f"adam step {t}")
+    with pytest.raises(mg.MggcnError):
+        mg.mggcn_adam_step(Wd, Wd, md, vd, 0)

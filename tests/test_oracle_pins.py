@@ -490,3 +490,24 @@ def test_epoch_with_injected_relu_decisions(ref):
     assert np.array_equal(WG3[1], WG[1])                 # last layer's gradient does not see the mask
     changed = np.any(WG3[0] != WG[0], axis=0)
     assert changed[b] and not np.any(np.delete(changed, b))
+
+
+def test_adam_against_closed_form_and_torch(ref):
+    import torch
+
+    rng = np.random.default_rng(4)
+    W0 = rng.standard_normal((13, 7))
+    grads = [rng.standard_normal((13, 7)) * 10.0 ** rng.integers(-4, 2) for _ in range(4)]
+    # first step from zero moments: the bias-corrected ratio is g / (|g| + eps) exactly
+    W, m, v = W0.copy(), np.zeros_like(W0), np.zeros_like(W0)
+    ref.adam_step(W, grads[0], m, v, 1, lr=0.05, eps=1e-8)
+    np.testing.assert_allclose(W, W0 - 0.05 * grads[0] / (np.abs(grads[0]) + 1e-8), rtol=1e-12)
+    # several steps against torch's optimiser in fp64
+    Wt = torch.from_numpy(W0.copy()).requires_grad_(True)
+    opt = torch.optim.Adam([Wt], lr=0.05, betas=(0.9, 0.999), eps=1e-8)
+    W, m, v = W0.copy(), np.zeros_like(W0), np.zeros_like(W0)
+    for t, g in enumerate(grads, start=1):
+        Wt.grad = torch.from_numpy(g.copy())
+        opt.step()
+        ref.adam_step(W, g, m, v, t, lr=0.05)
+        np.testing.assert_allclose(W, Wt.detach().numpy(), rtol=1e-11, atol=1e-13)
