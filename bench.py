@@ -36,12 +36,48 @@ def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
     return 8 * nnz + 4 * (n_rows + 1) + 4 * F * nnz + 4 * F * n_rows
 
 
+def spmm_sweep(args, cfg, mg, torch, dev) -> int:
+    """SpMM-only feature-width sweep (the density / width study of the paper's evaluation, on the
+    synthetic stand-in graphs)."""
+    widths = [int(x) for x in args.spmm_sweep.split(",")]
+    g = cfg.graph()
+    n = g.n_rows
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev))
+    nnz = int(colidx.numel())
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=max(widths), seg_len=args.seg_len)
+    rows = []
+    for F in widths:
+        ld = (F + 15) // 16 * 16
+        src = torch.randn((n, ld), device=dev)
+        dst = torch.empty((n, ld), device=dev)
+        for _ in range(2):
+            mg.mggcn_spmm(graph, mg.OP_N, src[:, :F], Y=dst[:, :F])
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        for a, b in evs:
+            a.record()
+            mg.mggcn_spmm(graph, mg.OP_N, src[:, :F], Y=dst[:, :F])
+            b.record()
+        torch.cuda.synchronize()
+        ms = min(a.elapsed_time(b) for a, b in evs)
+        beff = spmm_bytes(nnz, n, F)
+        rows.append({"F": F, "ms": round(ms, 4), "panels": graph.panels(F), "B_eff_GB": round(beff / 1e9, 2),
+                     "GBps_eff": round(beff / ms / 1e6, 1), "pct_hbm_peak": round(100 * beff / ms / 1e6 / HBM_PEAK_GBPS, 1),
+                     "gflops": round(2.0 * nnz * F / ms / 1e6, 1)})
+        del src, dst
+    print(json.dumps({"mode": "spmm-sweep", "config": args.config, "n": n, "nnz": nnz, "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large"])
+    ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large", "rmat"])
+    ap.add_argument("--spmm-sweep", default="", metavar="F1,F2,...",
+                    help="feature-width sweep mode: time the forward SpMM of the chosen configuration's graph at "
+                         "each width (HIP events, min of 10), print one JSON object, then exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seg-len", type=int, default=0)
     ap.add_argument("--profile-spmm", type=int, default=0, metavar="N",
@@ -66,10 +102,18 @@ def main() -> int:
     dims = cfg.dims
     L = len(dims) - 1
 
+    if args.spmm_sweep:
+        return spmm_sweep(args, cfg, mg, torch, dev)
+
     t0 = time.time()
     g = cfg.graph()
     n = g.n_rows
-    X = torch.from_numpy(cfg.features(n)).to(dev)
+    # X is stored with its rows padded to a multiple of 16 floats (602 -> 608): the layout any
+    # caller should pick, it keeps every row 64-byte aligned for the 16-byte load paths
+    d0p = (dims[0] + 15) // 16 * 16
+    Xbuf = torch.zeros((n, d0p), dtype=torch.float32, device=dev)
+    Xbuf[:, :dims[0]] = torch.from_numpy(cfg.features(n)).to(dev)
+    X = Xbuf[:, :dims[0]]
     Ws = [torch.from_numpy(w).to(dev) for w in cfg.weights()]
     labels = torch.from_numpy(cfg.labels(n)).to(dev)
     gen_s = time.time() - t0
@@ -192,7 +236,7 @@ def main() -> int:
                   f"call at F={Fdom} = {P} column-panel launches of it (+ the small row fix-up launches)",
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES,
+        "traffic": MEASURED_TRAFFIC_BYTES if args.config == "medium" else None,
         "launches_per_call": P,
         "algorithmic_bytes_per_launch": dom_bytes // P,
         "avg_launch_ms": round(dom_ms / P, 4),
@@ -213,7 +257,7 @@ def main() -> int:
             if not k.startswith("spmm"):
                 continue
             F = int(k.rsplit("F", 1)[1])
-            Xs = X[:, :F].cpu().numpy().astype(np.float64) if F <= X.shape[1] else None
+            Xs = (X[:, :F].cpu().numpy() if F <= X.shape[1] else wl.normal_f32(1, F, (n, F))).astype(np.float64)
             t0 = time.perf_counter()
             ref.spmm(ref.OP_T if "bwd" in k else ref.OP_N, n, n, rp, ci, v64, Xs)
             cpu_s += time.perf_counter() - t0

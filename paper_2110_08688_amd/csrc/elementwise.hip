@@ -2,6 +2,7 @@
 // fused epilogues, and the softmax cross-entropy loss with its gradient.
 #include "common.h"
 
+#include <algorithm>
 #include <cmath>
 
 namespace mggcn {
@@ -20,7 +21,9 @@ __global__ __launch_bounds__(kThreads) void relu_bwd_kernel(int64_t rows, int co
   if (!(act[i * lda + f] > 0.f)) G[i * ldg + f] = 0.f;
 }
 
-// T lanes (power of two, <= 64) per row; 64/T rows per wavefront.
+// T lanes (power of two, <= 64) per row; 64/T rows per wavefront per step; a fixed grid whose
+// wavefronts stride over the rows, so the number of loss partials stays small and every partial
+// is summed in a fixed order.
 __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(int64_t n, int C, int T,
                                                                const float* Z, int64_t ldz,
                                                                const int32_t* __restrict__ labels,
@@ -31,40 +34,43 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(int64_t n, int C, 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int rows_per_wave = 64 / T;
   const int tl = lane % T;
-  const int64_t row = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * rows_per_wave + lane / T;
-  const bool live = row < n;
-  const float* z = Z + (live ? row : 0) * ldz;
-
-  float mx = -INFINITY;
-  if (live)
-    for (int c = tl; c < C; c += T) mx = fmaxf(mx, z[c]);
-  for (int d = 1; d < T; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
-  float s = 0.f;
-  if (live)
-    for (int c = tl; c < C; c += T) s += expf(z[c] - mx);
-  for (int d = 1; d < T; d <<= 1) s += __shfl_xor(s, d);
-  float row_loss = 0.f;
-  float lse = 0.f, others = 0.f;
-  int y = -1;
-  if (live) {
-    lse = mx + logf(s);
-    y = labels[row];
-    for (int c = tl; c < C; c += T)
-      if (c != y) others += expf(z[c] - lse);
-  }
-  // softmax[y] - 1 = -(sum of the other classes): free of cancellation when softmax[y] -> 1
-  for (int d = 1; d < T; d <<= 1) others += __shfl_xor(others, d);
-  if (live) {
-    float* g = dZ + row * ldd;  // may be the same memory as z: each lane reads an element
-    for (int c = tl; c < C; c += T) {  // before it overwrites that same element
-      const float zc = z[c];
-      if (c == y) row_loss = lse - zc;
-      g[c] = (c == y ? -others : expf(zc - lse)) * inv_n;
+  const int64_t wave_gid = (int64_t)blockIdx.x * (kThreads / 64) + wave;
+  const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+  float loss_acc = 0.f;
+  for (int64_t base = wave_gid * rows_per_wave; base < n; base += n_waves * rows_per_wave) {
+    const int64_t row = base + lane / T;
+    const bool live = row < n;
+    const float* z = Z + (live ? row : 0) * ldz;
+    float mx = -INFINITY;
+    if (live)
+      for (int c = tl; c < C; c += T) mx = fmaxf(mx, z[c]);
+    for (int d = 1; d < T; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+    float s = 0.f;
+    if (live)
+      for (int c = tl; c < C; c += T) s += expf(z[c] - mx);
+    for (int d = 1; d < T; d <<= 1) s += __shfl_xor(s, d);
+    float lse = 0.f, others = 0.f;
+    int y = -1;
+    if (live) {
+      lse = mx + logf(s);
+      y = labels[row];
+      for (int c = tl; c < C; c += T)
+        if (c != y) others += expf(z[c] - lse);
+    }
+    // softmax[y] - 1 = -(sum of the other classes): free of cancellation when softmax[y] -> 1
+    for (int d = 1; d < T; d <<= 1) others += __shfl_xor(others, d);
+    if (live) {
+      float* g = dZ + row * ldd;  // may be the same memory as z: each lane reads an element
+      for (int c = tl; c < C; c += T) {  // before it overwrites that same element
+        const float zc = z[c];
+        if (c == y) loss_acc += lse - zc;
+        g[c] = (c == y ? -others : expf(zc - lse)) * inv_n;
+      }
     }
   }
   // fixed-order reduction: lanes by xor tree, wavefronts in index order
-  for (int d = 1; d < 64; d <<= 1) row_loss += __shfl_xor(row_loss, d);
-  if (lane == 0) wave_loss[wave] = row_loss;
+  for (int d = 1; d < 64; d <<= 1) loss_acc += __shfl_xor(loss_acc, d);
+  if (lane == 0) wave_loss[wave] = loss_acc;
   __syncthreads();
   if (threadIdx.x == 0) {
     float t = 0.f;
@@ -110,7 +116,7 @@ int team_lanes(int C) {
 
 int64_t loss_blocks(int64_t n, int C) {
   const int rows_per_block = (kThreads / 64) * (64 / team_lanes(C));
-  return ceil_div(n, rows_per_block);
+  return std::min<int64_t>(ceil_div(n, rows_per_block), 4096);
 }
 
 }  // namespace
