@@ -593,3 +593,46 @@ def test_adam_step(mg, dev, ref):
         assert_rows_close(Wd.cpu().numpy(), W, tol=1e-5, what=f"adam step {t}")
     with pytest.raises(mg.MggcnError):
         mg.mggcn_adam_step(Wd, Wd, md, vd, 0)
+
+
+def test_spmm_random_cases(mg, dev, ref):
+    """Seeded random small problems: rectangular shapes, random densities, widths, leading
+    dimensions, ops, beta, epilogues, segment lengths and panel counts."""
+    import scipy.sparse as sp
+    import torch
+
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        nr, nc = int(rng.integers(1, 400)), int(rng.integers(1, 400))
+        dens = float(rng.choice([0.0, 0.01, 0.1, 0.5]))
+        S = sp.random(nr, nc, density=dens, format="csr", random_state=int(rng.integers(1 << 30)), dtype=np.float32)
+        S.sort_indices()
+        rp, ci, va = S.indptr.astype(np.int32), S.indices.astype(np.int32), S.data.astype(np.float32)
+        F = int(rng.choice([1, 2, 5, 8, 16, 33, 41, 64, 100, 128, 130, 300]))
+        ldx, ldy = F + int(rng.integers(0, 9)), F + int(rng.integers(0, 9))
+        op = int(rng.integers(0, 2))
+        beta = float(rng.integers(0, 2))
+        epi = int(rng.choice([mg.EPI_NONE, mg.EPI_RELU, mg.EPI_RELU_MASK])) if beta == 0 else int(rng.choice([mg.EPI_NONE, mg.EPI_RELU]))
+        seg, P = int(rng.choice([0, 8, 50])), int(rng.choice([0, 1, 3, 8]))
+        say(f"[spmm random {case}] {nr}x{nc} dens={dens} F={F} ldx={ldx} ldy={ldy} op={op} beta={beta} epi={epi} seg={seg} P={P}")
+        d = [to_dev(a, dev) for a in (rp, ci, va)]
+        t = mg.mggcn_csr_transpose(nr, nc, *d)
+        G = mg.Graph(nr, nc, *d, transpose=t, F_max=max(F, 1), seg_len=seg, n_panels=P)
+        xin, yout = (nc, nr) if op == mg.OP_N else (nr, nc)
+        Xp = wl.normal_f32(case, 1, (xin, ldx))
+        Y0 = wl.normal_f32(case, 2, (yout, ldy))
+        Yd = to_dev(Y0, dev)
+        mg.mggcn_spmm(G, op, to_dev(Xp, dev)[:, :F], beta=beta, epilogue=epi, Y=Yd[:, :F])
+        got = Yd.cpu().numpy()
+        want = ref.spmm(op, nr, nc, rp, ci, va.astype(np.float64), Xp[:, :F].astype(np.float64), beta=beta,
+                        Y=Y0[:, :F].astype(np.float64).copy())
+        if epi == mg.EPI_RELU:
+            want = np.maximum(want, 0.0)
+        elif epi == mg.EPI_RELU_MASK:
+            want = np.where(Y0[:, :F] > 0, want, 0.0)
+        scale = ref.spmm(op, nr, nc, rp, ci, np.abs(va).astype(np.float64), np.abs(Xp[:, :F]).astype(np.float64))
+        scale = scale + beta * np.abs(Y0[:, :F])
+        err = np.abs(got[:, :F] - want)
+        # forward error bound of the row sums (random sparse values cancel, so compare against |A||X|)
+        assert np.all(err <= 1e-5 * np.maximum(scale.max(axis=1, keepdims=True), 1e-30)), f"case {case}: {err.max()}"
+        assert np.array_equal(got[:, F:], Y0[:, F:])
