@@ -207,18 +207,28 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
     LoadB::template store<LDB>(Bs, rb);
     __syncthreads();
     if (k0 + BK < ke) load_step(k0 + BK);  // in flight during the MFMA loop below
+    // all fragments of the step are read from LDS first, then the MFMAs run back to back
+    float a[BK / 2][TM], b[BK / 2][TN];
 #pragma unroll
     for (int kk = 0; kk < BK; kk += 2) {
-      float a[TM], b[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = As[kk + frow][(wm * TM + i) * 32 + fcol];
+      for (int i = 0; i < TM; ++i) a[kk / 2][i] = As[kk + frow][(wm * TM + i) * 32 + fcol];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = Bs[kk + frow][(wn * TN + j) * 32 + fcol];
+      for (int j = 0; j < TN; ++j) b[kk / 2][j] = Bs[kk + frow][(wn * TN + j) * 32 + fcol];
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2)
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk / 2][i], b[kk / 2][j], acc[i][j], 0, 0, 0);
+    // ask the scheduler for LDS reads that run a few k-pairs ahead of the MFMAs consuming them
+    __builtin_amdgcn_sched_group_barrier(0x100, 4 * 2, 0);
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 2) {
+      __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     }
     __syncthreads();
   }
