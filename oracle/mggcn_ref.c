@@ -14,6 +14,11 @@
  *     pins are in tests/test_oracle_*.py (dense brute force, closed forms,
  *     scipy / numpy / torch-autograd third opinions, finite differences).
  *   - Readings of points the paper leaves open are marked "Reading:".
+ *   - One extension beyond the paper: an epoch whose SpMMs gather a bfloat16 copy of their
+ *     dense operand (mggcn_ref_bf16_*, mggcn_ref_epoch_bf16).  The rounding is the IEEE
+ *     definition written out and is pinned by hand-worked values, by an exhaustive check
+ *     against the neighbour definition and by torch's conversion; the epoch is pinned by a
+ *     numpy / scipy re-composition of the same chain.
  *
  * Parallelism: OpenMP over independent output rows (or output columns for the
  * scatter form) only, so every output element is summed in the same order as
@@ -193,6 +198,84 @@ int mggcn_ref_spmm(int op, int n_rows, int n_cols, const int32_t* rowptr, const 
 }
 
 /* ------------------------------------------------------------------------
+ * Lower-precision gathered operand: the dense operand of an SpMM held as bfloat16 (sign, 8
+ * exponent bits, 7 fraction bits: a float32 whose low 16 bits are zero), products and sums
+ * still exact here.  This is an extension beyond the paper, which keeps everything in fp32.
+ *
+ * Rounding float32 -> bfloat16 is IEEE round-to-nearest, ties to even, written out as its
+ * definition: take the two bfloat16 neighbours of x (toward zero and away from zero), return
+ * the nearer one, and on a tie the one whose last fraction bit is 0.  A value at least half a
+ * step above the largest finite bfloat16 goes to infinity; a NaN stays a NaN.
+ * --------------------------------------------------------------------- */
+static float f32_from_bits(uint32_t u) { float f; memcpy(&f, &u, sizeof f); return f; }
+
+uint16_t mggcn_ref_bf16_code(float x) {
+  uint32_t u;
+  memcpy(&u, &x, sizeof u);
+  if ((u & 0x7F800000u) == 0x7F800000u) {            /* infinity or NaN */
+    if (u & 0x007FFFFFu) return (uint16_t)((u >> 16) | 0x0040u); /* keep a NaN a (quiet) NaN */
+    return (uint16_t)(u >> 16);
+  }
+  const uint32_t lo = u & 0xFFFF0000u;                /* neighbour toward zero */
+  if (lo == u) return (uint16_t)(u >> 16);            /* already representable */
+  const uint32_t hi = lo + 0x00010000u;               /* neighbour away from zero */
+  const double ax = fabs((double)x);
+  const double alo = fabs((double)f32_from_bits(lo));
+  /* beyond the largest finite value the next step of the same size is 2^128 */
+  const double ahi = ((hi & 0x7FFFFFFFu) == 0x7F800000u) ? ldexp(1.0, 128) : fabs((double)f32_from_bits(hi));
+  const double below = ax - alo, above = ahi - ax;    /* both exact in double */
+  if (below < above) return (uint16_t)(lo >> 16);
+  if (above < below) return (uint16_t)(hi >> 16);
+  return (uint16_t)((((lo >> 16) & 1u) == 0u ? lo : hi) >> 16);
+}
+
+float mggcn_ref_bf16_value(uint16_t code) { return f32_from_bits((uint32_t)code << 16); }
+
+/* codes_out / values_out may each be NULL */
+void mggcn_ref_bf16_round(int64_t count, const float* in, uint16_t* codes_out, float* values_out) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) {
+    const uint16_t c = mggcn_ref_bf16_code(in[i]);
+    if (codes_out) codes_out[i] = c;
+    if (values_out) values_out[i] = mggcn_ref_bf16_value(c);
+  }
+}
+
+/* What one SpMM of a chain does about its operand.  bf16 == 0: nothing (the fp32 path).
+   Otherwise the rows x F operand is replaced, before the product, by
+     inject != NULL : the bfloat16 codes handed in (dense, ld = F).  Used for chain-level parity:
+                      which neighbour a value within rounding of a tie goes to is a discrete
+                      decision, comparable only when both sides take it from the same numbers
+                      (the device's fp32 values);
+     inject == NULL : the oracle's own value, rounded to float32 and then to bfloat16.
+   record != NULL receives the oracle's own codes either way, so that a test can see how far
+   the injected ones are from them. */
+typedef struct {
+  int bf16;
+  const uint16_t* inject;
+  uint16_t* record;
+} RefGather;
+
+static int spmm_gathered(const RefGather* q, int op, int n_rows, int n_cols, const int32_t* rowptr,
+                         const int32_t* colidx, const double* val, const double* X, int64_t ldx, int F,
+                         double* Y, int64_t ldy) {
+  if (!q || !q->bf16) return mggcn_ref_spmm(op, n_rows, n_cols, rowptr, colidx, val, X, ldx, F, 0.0, Y, ldy);
+  const int64_t rows = (op == REF_OP_N) ? n_cols : n_rows;
+  double* Xq = (double*)malloc(sizeof(double) * (size_t)(rows > 0 ? rows : 1) * (size_t)(F > 0 ? F : 1));
+  if (!Xq) return REF_E_MEM;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < rows; ++i)
+    for (int f = 0; f < F; ++f) {
+      const uint16_t own = mggcn_ref_bf16_code((float)X[i * ldx + f]);
+      if (q->record) q->record[i * F + f] = own;
+      Xq[i * F + f] = (double)mggcn_ref_bf16_value(q->inject ? q->inject[i * F + f] : own);
+    }
+  const int rc = mggcn_ref_spmm(op, n_rows, n_cols, rowptr, colidx, val, Xq, F, F, 0.0, Y, ldy);
+  free(Xq);
+  return rc;
+}
+
+/* ------------------------------------------------------------------------
  * GeMM (Eq. 5, 10, 11):  C = op(A) * op(B) + beta * C,  C is M x N, inner K.
  *   opA = N: A is M x K;  opA = T: A is K x M (used as its transpose)
  *   opB = N: B is K x N;  opB = T: B is N x K
@@ -285,25 +368,31 @@ static double* dalloc(int64_t rows, int64_t cols) {
  *   order SPMM_FIRST:  P  = A^*H_in ; Z = P*W
  * A^ is n x n here (square graph), op N.  relu != 0 applies Eq. 7.
  * --------------------------------------------------------------------- */
-int mggcn_ref_layer_fwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
-                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
-                        const double* W, int64_t ldw, double* H_out, int64_t ldo) {
+static int layer_fwd_impl(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                          int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                          const double* W, int64_t ldw, double* H_out, int64_t ldo, const RefGather* q) {
   int rc;
   if (order == REF_GEMM_FIRST) {
     double* HW = dalloc(n, d_out);
     if (!HW) return REF_E_MEM;
     rc = mggcn_ref_gemm(REF_OP_N, REF_OP_N, n, d_out, d_in, H_in, ldh, W, ldw, 0.0, HW, d_out);
-    if (!rc) rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, HW, d_out, d_out, 0.0, H_out, ldo);
+    if (!rc) rc = spmm_gathered(q, REF_OP_N, n, n, rowptr, colidx, val, HW, d_out, d_out, H_out, ldo);
     free(HW);
   } else {
     double* P = dalloc(n, d_in);
     if (!P) return REF_E_MEM;
-    rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, 0.0, P, d_in);
+    rc = spmm_gathered(q, REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, P, d_in);
     if (!rc) rc = mggcn_ref_gemm(REF_OP_N, REF_OP_N, n, d_out, d_in, P, d_in, W, ldw, 0.0, H_out, ldo);
     free(P);
   }
   if (!rc && relu) mggcn_ref_relu(n, d_out, H_out, ldo);
   return rc;
+}
+
+int mggcn_ref_layer_fwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                        const double* W, int64_t ldw, double* H_out, int64_t ldo) {
+  return layer_fwd_impl(n, rowptr, colidx, val, d_in, d_out, order, relu, H_in, ldh, W, ldw, H_out, ldo, NULL);
 }
 
 /* ------------------------------------------------------------------------
@@ -317,34 +406,44 @@ int mggcn_ref_layer_fwd(int n, const int32_t* rowptr, const int32_t* colidx, con
  *   SPMM_FIRST:  P = A^ H_in ; W_G = P^T Z_G ; U = Z_G W^T ; H_G = A^^T U
  * G is overwritten by Z_G.  H_G may be NULL (first layer: no input gradient).
  * --------------------------------------------------------------------- */
-int mggcn_ref_layer_bwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
-                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
-                        const double* H_out, int64_t ldo, double* G, int64_t ldg, const double* W,
-                        int64_t ldw, double* W_G, int64_t ldwg, double* H_G, int64_t ldhg) {
+static int layer_bwd_impl(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                          int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                          const double* H_out, int64_t ldo, double* G, int64_t ldg, const double* W,
+                          int64_t ldw, double* W_G, int64_t ldwg, double* H_G, int64_t ldhg,
+                          const RefGather* q_fwd /* the layer's forward SpMM, redone for P */,
+                          const RefGather* q_bwd /* its backward SpMM */) {
   int rc = REF_OK;
   if (relu) mggcn_ref_relu_bwd(n, d_out, H_out, ldo, G, ldg);
   if (order == REF_GEMM_FIRST) {
     double* T = dalloc(n, d_out);
     if (!T) return REF_E_MEM;
-    rc = mggcn_ref_spmm(REF_OP_T, n, n, rowptr, colidx, val, G, ldg, d_out, 0.0, T, d_out);
+    rc = spmm_gathered(q_bwd, REF_OP_T, n, n, rowptr, colidx, val, G, ldg, d_out, T, d_out);
     if (!rc) rc = mggcn_ref_gemm(REF_OP_T, REF_OP_N, d_in, d_out, n, H_in, ldh, T, d_out, 0.0, W_G, ldwg);
     if (!rc && H_G) rc = mggcn_ref_gemm(REF_OP_N, REF_OP_T, n, d_in, d_out, T, d_out, W, ldw, 0.0, H_G, ldhg);
     free(T);
   } else {
     double* P = dalloc(n, d_in);
     if (!P) return REF_E_MEM;
-    rc = mggcn_ref_spmm(REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, 0.0, P, d_in);
+    rc = spmm_gathered(q_fwd, REF_OP_N, n, n, rowptr, colidx, val, H_in, ldh, d_in, P, d_in);
     if (!rc) rc = mggcn_ref_gemm(REF_OP_T, REF_OP_N, d_in, d_out, n, P, d_in, G, ldg, 0.0, W_G, ldwg);
     free(P);
     if (!rc && H_G) {
       double* U = dalloc(n, d_in);
       if (!U) return REF_E_MEM;
       rc = mggcn_ref_gemm(REF_OP_N, REF_OP_T, n, d_in, d_out, G, ldg, W, ldw, 0.0, U, d_in);
-      if (!rc) rc = mggcn_ref_spmm(REF_OP_T, n, n, rowptr, colidx, val, U, d_in, d_in, 0.0, H_G, ldhg);
+      if (!rc) rc = spmm_gathered(q_bwd, REF_OP_T, n, n, rowptr, colidx, val, U, d_in, d_in, H_G, ldhg);
       free(U);
     }
   }
   return rc;
+}
+
+int mggcn_ref_layer_bwd(int n, const int32_t* rowptr, const int32_t* colidx, const double* val,
+                        int d_in, int d_out, int order, int relu, const double* H_in, int64_t ldh,
+                        const double* H_out, int64_t ldo, double* G, int64_t ldg, const double* W,
+                        int64_t ldw, double* W_G, int64_t ldwg, double* H_G, int64_t ldhg) {
+  return layer_bwd_impl(n, rowptr, colidx, val, d_in, d_out, order, relu, H_in, ldh, H_out, ldo, G, ldg, W, ldw,
+                        W_G, ldwg, H_G, ldhg, NULL, NULL);
 }
 
 /* ------------------------------------------------------------------------
@@ -357,10 +456,12 @@ int mggcn_ref_layer_bwd(int n, const int32_t* rowptr, const int32_t* colidx, con
  *               (see mggcn_ref_apply_mask); the forward pass always uses Eq. 7 as is.
  * Outputs: *loss, W_G[l] (same shapes as W[l]); logits_out (n x dims[L]) optional.
  * --------------------------------------------------------------------- */
-int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
-                    const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
-                    const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
-                    double* logits_out, const uint8_t* const* relu_masks) {
+static int epoch_impl(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
+                      const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
+                      const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
+                      double* logits_out, const uint8_t* const* relu_masks, int bf16,
+                      const uint16_t* const* fwd_in, const uint16_t* const* bwd_in,
+                      uint16_t* const* fwd_out, uint16_t* const* bwd_out) {
   if (L < 1) return REF_E_ARG;
   int rc = REF_OK;
   double** H = (double**)calloc((size_t)L + 1, sizeof(double*)); /* H[l] = input of layer l */
@@ -370,9 +471,10 @@ int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const d
     H[l + 1] = dalloc(n, dims[l + 1]);
     if (!H[l + 1]) { rc = REF_E_MEM; break; }
     const int ord = orders ? orders[l] : mggcn_ref_order(dims[l], dims[l + 1]);
-    rc = mggcn_ref_layer_fwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, l + 1 < L,
-                             l == 0 ? X : H[l], l == 0 ? ldx : dims[l], W[l], dims[l + 1], H[l + 1],
-                             dims[l + 1]);
+    const RefGather q = {bf16, fwd_in ? fwd_in[l] : NULL, fwd_out ? fwd_out[l] : NULL};
+    rc = layer_fwd_impl(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, l + 1 < L,
+                        l == 0 ? X : H[l], l == 0 ? ldx : dims[l], W[l], dims[l + 1], H[l + 1],
+                        dims[l + 1], &q);
   }
   double* G = NULL;
   if (!rc) {
@@ -390,9 +492,11 @@ int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const d
       mggcn_ref_apply_mask(n, dims[l + 1], relu_masks[l], G, dims[l + 1]);
       own_relu = 0;
     }
-    rc = mggcn_ref_layer_bwd(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, own_relu,
-                             l == 0 ? X : H[l], l == 0 ? ldx : dims[l], H[l + 1], dims[l + 1], G,
-                             dims[l + 1], W[l], dims[l + 1], W_G[l], dims[l + 1], HG, dims[l]);
+    const RefGather qf = {bf16, fwd_in ? fwd_in[l] : NULL, NULL};
+    const RefGather qb = {bf16, bwd_in ? bwd_in[l] : NULL, bwd_out ? bwd_out[l] : NULL};
+    rc = layer_bwd_impl(n, rowptr, colidx, val, dims[l], dims[l + 1], ord, own_relu,
+                        l == 0 ? X : H[l], l == 0 ? ldx : dims[l], H[l + 1], dims[l + 1], G,
+                        dims[l + 1], W[l], dims[l + 1], W_G[l], dims[l + 1], HG, dims[l], &qf, &qb);
     free(G);
     G = HG;
   }
@@ -400,6 +504,32 @@ int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const d
   for (int l = 1; l <= L; ++l) free(H[l]);
   free(H);
   return rc;
+}
+
+int mggcn_ref_epoch(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
+                    const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
+                    const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
+                    double* logits_out, const uint8_t* const* relu_masks) {
+  return epoch_impl(n, rowptr, colidx, val, L, dims, orders, X, ldx, labels, W, loss, W_G, logits_out,
+                    relu_masks, 0, NULL, NULL, NULL, NULL);
+}
+
+/* The same epoch with every SpMM gathering a bfloat16 copy of its dense operand (see RefGather).
+ * Per layer l the operand of the forward SpMM is n x (dims[l+1] if GeMM first, dims[l] if SpMM
+ * first), that of the backward SpMM n x (dims[l+1] if GeMM first: the gradient Z_G; dims[l] if
+ * SpMM first: U = Z_G W^T, formed only for l > 0).  fwd_in / bwd_in: NULL, or L pointers (each
+ * NULL or dense codes, ld = width) to use as those operands; fwd_out / bwd_out: NULL, or L
+ * pointers (each NULL or room for the codes) that receive the oracle's own roundings.
+ * Gradients treat the rounding as the identity (it is applied to values, not differentiated).
+ */
+int mggcn_ref_epoch_bf16(int n, const int32_t* rowptr, const int32_t* colidx, const double* val, int L,
+                         const int32_t* dims, const int32_t* orders, const double* X, int64_t ldx,
+                         const int32_t* labels, const double* const* W, double* loss, double* const* W_G,
+                         double* logits_out, const uint8_t* const* relu_masks,
+                         const uint16_t* const* fwd_in, const uint16_t* const* bwd_in,
+                         uint16_t* const* fwd_out, uint16_t* const* bwd_out) {
+  return epoch_impl(n, rowptr, colidx, val, L, dims, orders, X, ldx, labels, W, loss, W_G, logits_out,
+                    relu_masks, 1, fwd_in, bwd_in, fwd_out, bwd_out);
 }
 
 /* ------------------------------------------------------------------------

@@ -63,6 +63,11 @@ def _load():
         ]
         lib.mggcn_ref_epoch.restype = i32
         lib.mggcn_ref_epoch.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp]
+        lib.mggcn_ref_epoch_bf16.restype = i32
+        lib.mggcn_ref_epoch_bf16.argtypes = [i32, vp, vp, vp, i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp,
+                                             vp, vp, vp, vp]
+        lib.mggcn_ref_bf16_round.restype = None
+        lib.mggcn_ref_bf16_round.argtypes = [i64, vp, vp, vp]
         lib.mggcn_ref_adam_step.restype = i32
         lib.mggcn_ref_adam_step.argtypes = [i64, vp, vp, vp, vp, i32, dbl, dbl, dbl, dbl]
         _lib = lib
@@ -263,6 +268,78 @@ def epoch(n, rowptr, colidx, val, X, labels, Ws, orders=None, want_logits=False,
         "epoch",
     )
     return loss.value, WG, logits
+
+
+def bf16_round(x):
+    """float32 array -> (bfloat16 codes as uint16, the rounded values as float32), same shape."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    codes = np.empty(x.shape, dtype=np.uint16)
+    values = np.empty(x.shape, dtype=np.float32)
+    _load().mggcn_ref_bf16_round(x.size, x.ctypes.data, codes.ctypes.data, values.ctypes.data)
+    return codes, values
+
+
+def gather_widths(dims, orders):
+    """Per layer: (width of the forward SpMM's operand, width of the backward SpMM's operand or 0)."""
+    out = []
+    for l in range(len(dims) - 1):
+        o = orders[l] if orders is not None else order(int(dims[l]), int(dims[l + 1]))
+        if o == GEMM_FIRST:
+            out.append((int(dims[l + 1]), int(dims[l + 1])))
+        else:
+            out.append((int(dims[l]), int(dims[l]) if l > 0 else 0))
+    return out
+
+
+def epoch_bf16(n, rowptr, colidx, val, X, labels, Ws, orders=None, relu_masks=None, fwd_codes=None,
+               bwd_codes=None):
+    """The epoch with every SpMM gathering a bfloat16 copy of its operand.
+    fwd_codes / bwd_codes: optional lists of L entries (None or (n, width) uint16 arrays) used as the
+    operands instead of the oracle's own roundings.
+    -> (loss, [W_G...], own_fwd_codes, own_bwd_codes)  (own_*[l] is None where layer l has no such SpMM)"""
+    rowptr, colidx, val, X, labels = _i32(rowptr), _i32(colidx), _f64(val), _f64(X), _i32(labels)
+    Ws = [_f64(w) for w in Ws]
+    L = len(Ws)
+    dims = np.array([Ws[0].shape[0]] + [w.shape[1] for w in Ws], dtype=np.int32)
+    WG = [np.zeros_like(w) for w in Ws]
+    Wp = (C.c_void_p * L)(*[w.ctypes.data for w in Ws])
+    WGp = (C.c_void_p * L)(*[w.ctypes.data for w in WG])
+    ords = None if orders is None else _i32(orders)
+    loss = C.c_double(0.0)
+    Mp = None
+    if relu_masks is not None:
+        assert len(relu_masks) == L - 1
+        relu_masks = [np.ascontiguousarray(m, dtype=np.uint8) for m in relu_masks]
+        Mp = (C.c_void_p * max(L - 1, 1))(*[m.ctypes.data for m in relu_masks])
+    widths = gather_widths(dims, None if orders is None else list(orders))
+
+    def ptrs(given, which):
+        if given is None:
+            return None, None
+        keep = []
+        for l in range(L):
+            a = given[l]
+            if a is not None:
+                a = np.ascontiguousarray(a, dtype=np.uint16)
+                assert a.shape == (n, widths[l][which]), (a.shape, widths[l])
+            keep.append(a)
+        return (C.c_void_p * L)(*[None if a is None else a.ctypes.data for a in keep]), keep
+
+    fin, _k1 = ptrs(fwd_codes, 0)
+    bin_, _k2 = ptrs(bwd_codes, 1)
+    own_f = [np.zeros((n, w[0]), dtype=np.uint16) for w in widths]
+    own_b = [np.zeros((n, w[1]), dtype=np.uint16) if w[1] else None for w in widths]
+    fout = (C.c_void_p * L)(*[a.ctypes.data for a in own_f])
+    bout = (C.c_void_p * L)(*[None if a is None else a.ctypes.data for a in own_b])
+    _check(
+        _load().mggcn_ref_epoch_bf16(
+            n, rowptr.ctypes.data, colidx.ctypes.data, val.ctypes.data, L, dims.ctypes.data,
+            None if ords is None else ords.ctypes.data, X.ctypes.data, _ld(X), labels.ctypes.data,
+            Wp, C.byref(loss), WGp, None, Mp, fin, bin_, fout, bout,
+        ),
+        "epoch_bf16",
+    )
+    return loss.value, WG, own_f, own_b
 
 
 def adam_step(W, G, m, v, t, lr=1e-3, b1=0.9, b2=0.999, eps=1e-8):

@@ -511,3 +511,162 @@ def test_adam_against_closed_form_and_torch(ref):
         opt.step()
         ref.adam_step(W, g, m, v, t, lr=0.05)
         np.testing.assert_allclose(W, Wt.detach().numpy(), rtol=1e-11, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# bfloat16 copy of the gathered operand (extension beyond the paper's fp32)
+# ----------------------------------------------------------------------------
+
+def _f32_from_bits(bits):
+    return np.array(bits, dtype=np.uint32).view(np.float32)
+
+
+def test_bf16_round_worked_values(ref):
+    """Hand-worked roundings.  bfloat16 keeps 7 fraction bits, so its step at 1.0 is 2^-7."""
+    cases = [
+        (1.0, 0x3F80),
+        (1.0 + 2.0 ** -8, 0x3F80),                 # tie between 1 and 1+2^-7: even fraction (0) wins
+        (1.0 + 2.0 ** -8 + 2.0 ** -23, 0x3F81),    # just above the tie
+        (1.0 + 2.0 ** -7 + 2.0 ** -8, 0x3F82),     # tie between fractions 1 and 2: even (2) wins
+        (-(1.0 + 2.0 ** -8), 0xBF80),              # sign does not change the choice
+        (0.0, 0x0000),
+        (-0.0, 0x8000),
+        (np.inf, 0x7F80),
+        (-np.inf, 0xFF80),
+        (3.0, 0x4040),
+        (0.1, 0x3DCD),                             # 0.1f = 0x3DCCCCCD: low half 0xCCCD > 0x8000 -> up
+    ]
+    x = np.array([c[0] for c in cases], dtype=np.float32)
+    codes, values = ref.bf16_round(x)
+    assert [int(c) for c in codes] == [c[1] for c in cases]
+    assert np.array_equal(values.view(np.uint32), codes.astype(np.uint32) << 16)
+    # largest finite float32 is more than half a step above the largest finite bfloat16 -> infinity;
+    # the largest bfloat16 itself and anything below its upper tie stay finite
+    big = _f32_from_bits([0x7F7FFFFF, 0x7F7F0000, 0x7F7F7FFF, 0x7F7F8000])
+    codes, _ = ref.bf16_round(big)
+    assert [int(c) for c in codes] == [0x7F80, 0x7F7F, 0x7F7F, 0x7F80]
+    # subnormal float32: same rule on the bit pattern (steps are uniform there)
+    sub = _f32_from_bits([0x00000001, 0x00008000, 0x00008001, 0x00018000, 0x807FFFFF])
+    codes, _ = ref.bf16_round(sub)
+    assert [int(c) for c in codes] == [0x0000, 0x0000, 0x0001, 0x0002, 0x8080]
+    # NaN stays NaN
+    codes, values = ref.bf16_round(_f32_from_bits([0x7FC00000, 0x7F800001, 0xFFFFFFFF]))
+    assert np.all(np.isnan(values))
+
+
+def test_bf16_round_against_integer_rule_and_torch(ref):
+    """Every upper half-word with the low half-words around the tie, plus random bit patterns:
+    compared with the rule stated on integers (magnitude m = q*2^16 + r: round q up iff r > 2^15, or
+    r == 2^15 and q odd) and with torch's float32 -> bfloat16 conversion."""
+    import torch
+
+    hi = np.arange(1 << 16, dtype=np.uint32) << 16
+    lows = np.array([0x0000, 0x0001, 0x7FFF, 0x8000, 0x8001, 0xFFFF], dtype=np.uint32)
+    bits = (hi[:, None] | lows[None, :]).ravel()
+    rng = np.random.default_rng(11)
+    bits = np.concatenate([bits, rng.integers(0, 1 << 32, size=2_000_000, dtype=np.uint64).astype(np.uint32)])
+    x = bits.view(np.float32)
+    codes, values = ref.bf16_round(x)
+    finite = np.isfinite(x)
+    mag = (bits & 0x7FFFFFFF).astype(np.int64)
+    q, r = mag >> 16, mag & 0xFFFF
+    q = q + ((r > 0x8000) | ((r == 0x8000) & (q & 1 == 1)))
+    want = ((bits >> 31).astype(np.int64) << 15) | q
+    assert np.array_equal(codes[finite].astype(np.int64), want[finite])
+    t = torch.from_numpy(x.copy()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(codes[finite], t[finite])
+    assert np.all(np.isnan(values[np.isnan(x)]))
+    assert np.array_equal(values[np.isinf(x)], x[np.isinf(x)])
+    # properties of a rounding: idempotent, monotone, within half a step (at most 2^-8 relative for normal values)
+    again, _ = ref.bf16_round(values)
+    assert np.array_equal(again[finite], codes[finite])
+    xs = np.sort(x[finite])
+    _, vs = ref.bf16_round(xs)
+    assert np.all(vs[1:] >= vs[:-1])
+    normal = finite & (np.abs(x) >= 2.0 ** -126) & np.isfinite(values)
+    err = np.abs(values[normal].astype(np.float64) - x[normal].astype(np.float64))
+    assert np.all(err <= 2.0 ** -8 * np.abs(x[normal].astype(np.float64)))
+
+
+def _numpy_epoch_bf16(rp, ci, val, X, Ws, labels, n, orders):
+    """The bfloat16-gather epoch re-composed from scipy / numpy products, with torch's conversion as
+    the rounding: every SpMM sees its dense operand rounded float64 -> float32 -> bfloat16."""
+    import torch
+
+    def q(M):
+        t = torch.from_numpy(np.ascontiguousarray(M, dtype=np.float32)).to(torch.bfloat16)
+        return t.to(torch.float64).numpy()
+
+    A = sp.csr_matrix((val, ci, rp), shape=(n, n))
+    L = len(Ws)
+    H = [X]
+    for l in range(L):
+        Z = A @ q(H[l] @ Ws[l]) if orders[l] == 0 else (A @ q(H[l])) @ Ws[l]
+        H.append(np.maximum(Z, 0.0) if l + 1 < L else Z)
+    Z = H[L]
+    lse = np.log(np.exp(Z - Z.max(axis=1, keepdims=True)).sum(axis=1)) + Z.max(axis=1)
+    loss = float(np.mean(lse - Z[np.arange(n), labels]))
+    G = np.exp(Z - lse[:, None])
+    G[np.arange(n), labels] -= 1.0
+    G /= n
+    WG = [None] * L
+    for l in range(L - 1, -1, -1):
+        if l + 1 < L:
+            G = G * (H[l + 1] > 0)
+        if orders[l] == 0:
+            T = A.T @ q(G)
+            WG[l] = H[l].T @ T
+            G = T @ Ws[l].T
+        else:
+            WG[l] = (A @ q(H[l])).T @ G
+            G = A.T @ q(G @ Ws[l].T) if l > 0 else None
+    return loss, WG
+
+
+@pytest.mark.parametrize("dims,mode,sym", [((9, 6, 4), None, True), ((5, 11, 7, 3), None, True),
+                                            ((6, 6, 5), "mean", False), ((4, 9, 3), "mean", False)])
+def test_epoch_bf16_against_numpy_recomposition(ref, dims, mode, sym):
+    n = 37
+    m = ref.NORM_MEAN_IN if mode == "mean" else ref.NORM_SYM
+    rp, ci, val, X, Ws, labels = _setup_model(ref, n, dims, 7 + sum(dims), mode=m, symmetric=sym)
+    L = len(Ws)
+    auto = [ref.order(dims[l], dims[l + 1]) for l in range(L)]
+    for orders in (None, [ref.GEMM_FIRST] * L, [ref.SPMM_FIRST] * L):
+        loss, WG, own_f, own_b = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders)
+        want_loss, want_WG = _numpy_epoch_bf16(rp, ci, val, X, Ws, labels, n, auto if orders is None else orders)
+        assert abs(loss - want_loss) < 1e-12
+        for a, b in zip(WG, want_WG):
+            np.testing.assert_allclose(a, b, rtol=1e-10, atol=1e-13)
+        # it is a perturbation of the fp32-operand epoch of the size of the rounding step, not equal to it
+        loss32, WG32, _ = ref.epoch(n, rp, ci, val, X, labels, Ws, orders=orders)
+        assert loss != loss32 and abs(loss - loss32) < 2e-2 * abs(loss32)
+        for a, b in zip(WG, WG32):
+            assert np.max(np.abs(a - b)) < 5e-2 * np.max(np.abs(b))
+
+
+def test_epoch_bf16_recorded_and_injected_operands(ref):
+    n, dims = 33, (6, 10, 4)
+    rp, ci, val, X, Ws, labels = _setup_model(ref, n, dims, 99)
+    orders = [ref.SPMM_FIRST, ref.GEMM_FIRST]
+    loss, WG, own_f, own_b = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders)
+    # the recorded operands are the roundings of what the chain feeds its SpMMs
+    assert own_f[0].shape == (n, 6) and own_f[1].shape == (n, 4) and own_b[0] is None and own_b[1].shape == (n, 4)
+    assert np.array_equal(own_f[0], ref.bf16_round(X.astype(np.float32))[0])
+    _, xq = ref.bf16_round(X.astype(np.float32))
+    A = sp.csr_matrix((val, ci, rp), shape=(n, n))
+    H1 = np.maximum((A @ xq.astype(np.float64)) @ Ws[0], 0.0)
+    assert np.array_equal(own_f[1], ref.bf16_round((H1 @ Ws[1]).astype(np.float32))[0])
+    # handing the oracle its own roundings changes nothing
+    loss2, WG2, f2, b2 = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders, fwd_codes=own_f, bwd_codes=own_b)
+    assert loss2 == loss and all(np.array_equal(a, b) for a, b in zip(WG, WG2))
+    assert all(np.array_equal(a, b) for a, b in zip(own_f, f2))
+    # an all-zero operand for the last layer's forward SpMM gives zero logits: loss = ln C exactly
+    zero = [None, np.zeros((n, 4), dtype=np.uint16)]
+    loss3, _, f3, _ = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders, fwd_codes=zero)
+    assert abs(loss3 - math.log(4.0)) < 1e-15
+    assert np.array_equal(f3[1], own_f[1])  # what is recorded is still the oracle's own rounding
+    # moving one operand entry by one bfloat16 step moves the result, by about that step's share
+    bumped = [own_f[0].copy(), None]
+    bumped[0][3, 2] += 1
+    loss4, _, _, _ = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders, fwd_codes=bumped)
+    assert loss4 != loss and abs(loss4 - loss) < 1e-3
