@@ -119,8 +119,10 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * The CSR arrays are borrowed, not copied: they must outlive the handle.
  * seg_len = maximum entries per segment (0 = library default).
  * n_panels = number of column panels the SpMM walks one after the other so that all wavefronts
- * in flight gather from the same slice of X (0 = chosen from the matrix size and average row
- * length, and then used only for operands too large for the caches; 1 = never; > 1 = always).
+ * in flight gather from the same slice of X (0 = automatic: forms for 2, 4, 8, ... panels are
+ * built as far as the average row length affords, and each product picks the count that brings
+ * one panel of its gathered operand down to about 16 MiB, or none for a small operand;
+ * 1 = never; > 1 = always that many).
  * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
  * also holds the partial sums of rows that were cut, for feature widths up to F_max.
  * A handle may be re-bound; it must be bound before mggcn_spmm is called.
@@ -157,6 +159,24 @@ int mggcn_graph_panels(const mggcn_graph* g, int op /*mggcn_op*/, int32_t F);
 int mggcn_spmm(const mggcn_graph* g, int op /*mggcn_op*/, const float* X /*dev*/, int64_t ldx,
                int32_t F, float beta, int epilogue /*mggcn_epilogue*/, float* Y /*dev*/,
                int64_t ldy, void* stream);
+
+/* SpMM with a bfloat16 gathered operand -- an extension beyond the paper, whose operands are all
+ * fp32.  The product spends its memory traffic on gathering rows of X; holding X as bfloat16
+ * (the upper 16 bits of an fp32: 8 exponent, 7 fraction bits) halves it.  Values of A^ stay fp32,
+ * every product and sum is fp32, Y is fp32; given the same bfloat16 X the result meets the same
+ * error bound as mggcn_spmm, and against an fp32 X it differs by the rounding of X (relative
+ * 2^-8 per element at most).  Same arguments and rules as mggcn_spmm; X is n x F 2-byte elements
+ * with leading dimension ldx (elements).  A 16-byte aligned X with ldx a multiple of 8 (and a
+ * 16-byte aligned Y with ldy a multiple of 4) takes the wide path, anything else goes element
+ * by element. */
+int mggcn_spmm_bf16(const mggcn_graph* g, int op /*mggcn_op*/, const uint16_t* X /*dev, bfloat16*/,
+                    int64_t ldx, int32_t F, float beta, int epilogue /*mggcn_epilogue*/, float* Y /*dev*/,
+                    int64_t ldy, void* stream);
+
+/* fp32 -> bfloat16 copy of a rows x cols matrix, IEEE round to nearest, ties to even (overflow
+ * goes to infinity, a NaN stays a NaN).  Columns [cols, ldd) of dst are left untouched. */
+int mggcn_f32_to_bf16(int64_t rows, int32_t cols, const float* src /*dev*/, int64_t lds,
+                      uint16_t* dst /*dev*/, int64_t ldd, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * GeMM (Eq. 5, 10, 11):   C = epilogue( op(A) op(B) + beta C ),   C is M x N, inner size K
@@ -215,8 +235,12 @@ typedef struct mggcn_model mggcn_model;
  * once (mggcn_model_cache_input) and kept in the arena; the first layer then runs as
  * relu((A^ X) W) forward and W_G = (A^ X)^T Z_G backward with no SpMM at all in either pass --
  * the exact form of the paper's "saving one SpMM" (section "Order of Computation and Saving one
- * SpMM").  Costs one n x d_0 buffer. */
-enum { MGGCN_MODEL_CACHE_INPUT = 1 };
+ * SpMM").  Costs one n x d_0 buffer.
+ * MGGCN_MODEL_GATHER_BF16 (beyond the paper, which is fp32 throughout): every SpMM of the model
+ * gathers a bfloat16 copy of its dense operand, made by mggcn_f32_to_bf16 just before the product
+ * (see mggcn_spmm_bf16); GeMMs, activations, loss and all accumulation stay fp32.  The backward
+ * pass treats the rounding as the identity.  Costs one n x (widest SpMM) 2-byte buffer. */
+enum { MGGCN_MODEL_CACHE_INPUT = 1, MGGCN_MODEL_GATHER_BF16 = 2 };
 
 int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims /*host*/,
                        const int32_t* orders /*host or NULL*/, int32_t flags, mggcn_model** out);
@@ -235,6 +259,10 @@ int mggcn_model_order(const mggcn_model* m, int32_t l);
 /* device pointer and leading dimension of layer l's result buffer (its output H^(l+1),
  * later overwritten in place by the gradient with respect to it) */
 int mggcn_model_activation(const mggcn_model* m, int32_t l, float** ptr_out, int64_t* ld_out);
+/* With MGGCN_MODEL_GATHER_BF16: device pointer of the buffer that holds the bfloat16 operand of
+ * the most recent SpMM, and the leading dimension it has for an operand `width` columns wide
+ * (tests read the operand back between mggcn_layer_fwd / mggcn_layer_bwd calls). */
+int mggcn_model_gather_operand(const mggcn_model* m, int32_t width, uint16_t** ptr_out, int64_t* ld_out);
 
 /* One layer forward (Eq. 5-7): H_out = [relu]( A^ H_in W ).  H_in is n x d_l, W is
  * d_l x d_{l+1}, H_out is n x d_{l+1}; relu != 0 applies Eq. 7.  Uses the model's shared

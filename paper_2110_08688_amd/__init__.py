@@ -12,7 +12,7 @@ import ctypes as C
 from . import binding as B
 from .binding import (  # noqa: F401  (re-exported constants)
     EPI_NONE, EPI_RELU, EPI_RELU_MASK, NORM_MEAN_IN, NORM_SYM_SELFLOOP, OP_N, OP_T, ORDER_AUTO,
-    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MODEL_CACHE_INPUT, MggcnError,
+    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MODEL_CACHE_INPUT, MODEL_GATHER_BF16, MggcnError,
 )
 
 
@@ -141,6 +141,31 @@ def mggcn_spmm(graph: Graph, op, X, F=None, beta=0.0, epilogue=EPI_NONE, Y=None,
     return Y
 
 
+def mggcn_f32_to_bf16(src, dst=None, stream=None):
+    """bfloat16 copy (round to nearest even) of a 2-D fp32 tensor, as an int16 tensor of bit patterns."""
+    torch = _torch()
+    rows, cols = src.shape
+    if dst is None:
+        ld = (cols + 15) // 16 * 16
+        dst = torch.empty((rows, ld), dtype=torch.int16, device=src.device)[:, :cols]
+    B.check(B.lib().mggcn_f32_to_bf16(rows, cols, B.ptr(src), B.ld_of(src), B.ptr(dst), B.ld_of(dst),
+                                      _stream(stream)))
+    return dst
+
+
+def mggcn_spmm_bf16(graph: Graph, op, Xb, F=None, beta=0.0, epilogue=EPI_NONE, Y=None, stream=None):
+    """Y = epilogue(op(A^) X + beta Y) with X given as bfloat16 bit patterns (int16 tensor); Y is fp32."""
+    torch = _torch()
+    assert Xb.element_size() == 2
+    F = int(Xb.shape[1]) if F is None else F
+    out_rows = graph.n_rows if op == OP_N else graph.n_cols
+    if Y is None:
+        Y = torch.empty((out_rows, F), dtype=torch.float32, device=Xb.device)
+    B.check(B.lib().mggcn_spmm_bf16(graph.handle, op, B.ptr(Xb), B.ld_of(Xb), F, float(beta), epilogue, B.ptr(Y),
+                                    B.ld_of(Y), _stream(stream)))
+    return Y
+
+
 # ------------------------------------------------------------------------------------------
 # GeMM, ReLU', loss
 # ------------------------------------------------------------------------------------------
@@ -245,6 +270,17 @@ class Model:
         off = (p - base) // 4
         flat = self.arena[(base - self.arena.data_ptr()):].view(torch.float32)
         return flat[off: off + n * ld].view(n, ld)[:, :d].clone()
+
+    def gather_operand(self, width):
+        """MODEL_GATHER_BF16: a clone of the bfloat16 operand of the most recent SpMM, (n, width) int16."""
+        torch = _torch()
+        p, ld = C.c_void_p(None), C.c_int64(0)
+        B.check(B.lib().mggcn_model_gather_operand(self.handle, width, C.byref(p), C.byref(ld)))
+        n = self.graph.n_rows
+        base = self.arena.data_ptr()
+        off = p.value - base
+        flat = self.arena[off: off + n * ld.value * 2].view(torch.int16)
+        return flat.view(n, ld.value)[:, :width].clone()
 
     def close(self):
         if getattr(self, "handle", None):

@@ -18,7 +18,7 @@ NORM_SYM_SELFLOOP, NORM_MEAN_IN = 0, 1
 OP_N, OP_T = 0, 1
 EPI_NONE, EPI_RELU, EPI_RELU_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = -1, 0, 1
-MODEL_CACHE_INPUT = 1
+MODEL_CACHE_INPUT, MODEL_GATHER_BF16 = 1, 2
 
 _vp, _i32, _i64, _sz, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
 
@@ -38,6 +38,8 @@ SIGNATURES = {
     "mggcn_graph_panels": (C.c_int, [_vp, C.c_int, _i32]),
     "mggcn_graph_build_sweep": (C.c_int, [_vp, _i32, _i32, _vp]),
     "mggcn_spmm": (C.c_int, [_vp, C.c_int, _vp, _i64, _i32, _f32, C.c_int, _vp, _i64, _vp]),
+    "mggcn_spmm_bf16": (C.c_int, [_vp, C.c_int, _vp, _i64, _i32, _f32, C.c_int, _vp, _i64, _vp]),
+    "mggcn_f32_to_bf16": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),
     "mggcn_gemm_workspace_bytes": (_sz, [C.c_int, C.c_int, _i64, _i64, _i64]),
     "mggcn_gemm": (C.c_int, [C.c_int, C.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _f32, C.c_int, _vp, _i64,
                              _vp, _sz, _vp]),
@@ -53,6 +55,7 @@ SIGNATURES = {
     "mggcn_model_bind": (C.c_int, [_vp, _vp, _sz]),
     "mggcn_model_order": (C.c_int, [_vp, _i32]),
     "mggcn_model_activation": (C.c_int, [_vp, _i32, C.POINTER(_vp), C.POINTER(_i64)]),
+    "mggcn_model_gather_operand": (C.c_int, [_vp, _i32, C.POINTER(_vp), C.POINTER(_i64)]),
     "mggcn_layer_fwd": (C.c_int, [_vp, _i32, _vp, _i64, _vp, _i64, C.c_int, _vp, _i64, _vp]),
     "mggcn_layer_bwd": (C.c_int, [_vp, _i32, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64,
                                   C.c_int, _vp]),
@@ -115,5 +118,8 @@ def current_stream():
 
 def ld_of(t) -> int:
     """Leading dimension (elements) of a row-major 2-D tensor, possibly a column slice."""
-    assert t.dim() == 2 and (t.shape[1] <= 1 or t.stride(1) == 1), "need unit column stride"
+    assert t.dim() == 2
+    if t.numel() == 0:
+        return max(int(t.shape[1]), 1)
+    assert t.shape[1] <= 1 or t.stride(1) == 1, "need unit column stride"
     return max(int(t.stride(0)), int(t.shape[1]), 1) if t.shape[0] > 1 else max(int(t.shape[1]), 1)

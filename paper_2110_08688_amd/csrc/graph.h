@@ -76,7 +76,9 @@ struct Orientation {
   const int32_t* colidx = nullptr;
   const float* val = nullptr;
   TaskSet flat;      // one panel
-  TaskSet panelled;  // several column panels (absent when the analysis decides against it)
+  // Column-panel forms: either the one panel count the caller asked for, or one per power of two
+  // up to what the average row length affords; a product picks by the size of its gathered operand.
+  std::vector<TaskSet> panelled;
   SweepSet sweep;    // absent unless the graph is dense enough
 };
 
@@ -99,6 +101,7 @@ struct mggcn_graph {
   float* d_partial = nullptr;
   bool bound = false;
   int32_t chunk_lanes = 0;     // forced lanes per feature chunk (0 = widest)
-  int64_t panel_min_bytes = 0;  // gathered operand smaller than this: panels are not used
+  int64_t panel_bytes = 0;      // one column panel of the gathered operand should be about this large
+  bool panels_fixed = false;    // the caller chose the panel count: use it whatever the operand size
   bool sweep_forced = false;    // sweep form requested explicitly: use it whatever the operand size
 };

@@ -28,6 +28,8 @@ struct mggcn_model {
   char* arena = nullptr;
   bool cache_input = false;  // layer 0 works from a stored A^ X
   bool cache_valid = false;
+  bool gather_bf16 = false;  // every SpMM gathers a bfloat16 copy of its operand
+  size_t off_bf16 = 0;       // that copy: n x padded_ld(widest SpMM) 2-byte elements
 };
 
 namespace mggcn {
@@ -38,6 +40,18 @@ int64_t padded_ld(int32_t width) { return (int64_t)align_up((size_t)std::max(wid
 int resolve_order(int32_t d_in, int32_t d_out, int32_t requested) {
   if (requested == MGGCN_ORDER_GEMM_FIRST || requested == MGGCN_ORDER_SPMM_FIRST) return requested;
   return d_in < d_out ? MGGCN_ORDER_SPMM_FIRST : MGGCN_ORDER_GEMM_FIRST;
+}
+
+// The SpMM of a layer: straight from the fp32 operand, or (model flag) from a bfloat16 copy of it
+// made just before, which halves the bytes the product gathers.
+int gathered_spmm(const mggcn_model* m, int op, const float* X, int64_t ldx, int32_t F, int epi, float* Y,
+                  int64_t ldy, void* stream) {
+  if (!m->gather_bf16) return mggcn_spmm(m->g, op, X, ldx, F, 0.f, epi, Y, ldy, stream);
+  uint16_t* Xb = reinterpret_cast<uint16_t*>(m->arena + m->off_bf16);
+  const int64_t ldb = padded_ld(F);
+  const int rc = mggcn_f32_to_bf16(m->n, F, X, ldx, Xb, ldb, stream);
+  if (rc) return rc;
+  return mggcn_spmm_bf16(m->g, op, Xb, ldb, F, 0.f, epi, Y, ldy, stream);
 }
 
 int check_layer(const mggcn_model* m, int32_t l) {
@@ -71,7 +85,8 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   *out = nullptr;
   MGGCN_REQUIRE(g != nullptr && dims != nullptr, MGGCN_E_INVALID_ARG, "graph / dims is NULL");
   MGGCN_REQUIRE(L >= 1 && L <= 64, MGGCN_E_INVALID_ARG, "layer count %d outside [1, 64]", L);
-  MGGCN_REQUIRE((flags & ~MGGCN_MODEL_CACHE_INPUT) == 0, MGGCN_E_INVALID_ARG, "unknown model flags 0x%x", flags);
+  MGGCN_REQUIRE((flags & ~(MGGCN_MODEL_CACHE_INPUT | MGGCN_MODEL_GATHER_BF16)) == 0, MGGCN_E_INVALID_ARG,
+                "unknown model flags 0x%x", flags);
   MGGCN_REQUIRE(g->fwd.n_rows == g->fwd.n_cols, MGGCN_E_INVALID_ARG,
                 "a model needs a square graph, got %d x %d", g->fwd.n_rows, g->fwd.n_cols);
   for (int32_t l = 0; l <= L; ++l)
@@ -86,6 +101,7 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   m->n = g->fwd.n_rows;
   m->L = L;
   m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
+  m->gather_bf16 = (flags & MGGCN_MODEL_GATHER_BF16) != 0;
   m->dims.assign(dims, dims + L + 1);
   m->orders.resize(L);
   m->ld_act.resize(L);
@@ -114,6 +130,11 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   }
   m->off_tmp = off;
   off += align_up(n * (size_t)padded_ld(tmp_width) * sizeof(float), kWsAlign);
+  if (m->gather_bf16) {
+    const int32_t w = mggcn_model_spmm_width_max(dims, m->orders.data(), L, flags);
+    m->off_bf16 = off;
+    off += align_up(n * (size_t)padded_ld(w) * sizeof(uint16_t), kWsAlign);
+  }
   m->off_gemm_ws = off;
   off += align_up(m->gemm_ws_bytes, kWsAlign);
   m->loss_ws_bytes = mggcn_softmax_ce_workspace_bytes(m->n);
@@ -147,7 +168,7 @@ int mggcn_model_cache_input(mggcn_model* m, const float* X, int64_t ldx, void* s
   MGGCN_REQUIRE(m->arena != nullptr, MGGCN_E_WORKSPACE, "model is not bound to an arena");
   MGGCN_REQUIRE(X != nullptr && ldx >= m->dims[0], MGGCN_E_INVALID_ARG, "X is NULL or ldx < d_0");
   float* P = reinterpret_cast<float*>(m->arena + m->off_p[0]);
-  const int rc = mggcn_spmm(m->g, MGGCN_OP_N, X, ldx, m->dims[0], 0.f, MGGCN_EPI_NONE, P, m->ld_p[0], stream);
+  const int rc = gathered_spmm(m, MGGCN_OP_N, X, ldx, m->dims[0], MGGCN_EPI_NONE, P, m->ld_p[0], stream);
   if (rc) return rc;
   m->cache_valid = true;
   return MGGCN_OK;
@@ -165,6 +186,16 @@ int mggcn_model_activation(const mggcn_model* m, int32_t l, float** ptr_out, int
   MGGCN_REQUIRE(ptr_out && ld_out, MGGCN_E_INVALID_ARG, "ptr_out / ld_out is NULL");
   *ptr_out = reinterpret_cast<float*>(m->arena + m->off_act[l]);
   *ld_out = m->ld_act[l];
+  return MGGCN_OK;
+}
+
+int mggcn_model_gather_operand(const mggcn_model* m, int32_t width, uint16_t** ptr_out, int64_t* ld_out) {
+  MGGCN_REQUIRE(m != nullptr && ptr_out && ld_out, MGGCN_E_INVALID_ARG, "model / ptr_out / ld_out is NULL");
+  MGGCN_REQUIRE(m->gather_bf16, MGGCN_E_INVALID_ARG, "model was created without MGGCN_MODEL_GATHER_BF16");
+  MGGCN_REQUIRE(m->arena != nullptr, MGGCN_E_WORKSPACE, "model is not bound to an arena");
+  MGGCN_REQUIRE(width >= 1, MGGCN_E_INVALID_ARG, "width %d must be positive", width);
+  *ptr_out = reinterpret_cast<uint16_t*>(m->arena + m->off_bf16);
+  *ld_out = padded_ld(width);
   return MGGCN_OK;
 }
 
@@ -187,12 +218,12 @@ int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
     rc = mggcn_gemm(MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, H_in, ld_in, W, ldw, 0.f, MGGCN_EPI_NONE, tmp,
                     ldt, nullptr, 0, stream);
     if (rc) return rc;
-    return mggcn_spmm(m->g, MGGCN_OP_N, tmp, ldt, d_out, 0.f, epi, H_out, ld_out, stream);
+    return gathered_spmm(m, MGGCN_OP_N, tmp, ldt, d_out, epi, H_out, ld_out, stream);
   }
   // associativity:  P = A^ H ;  H' = relu(P W)
   float* P = reinterpret_cast<float*>(m->arena + m->off_p[l]);
   if (!cached) {
-    rc = mggcn_spmm(m->g, MGGCN_OP_N, H_in, ld_in, d_in, 0.f, MGGCN_EPI_NONE, P, m->ld_p[l], stream);
+    rc = gathered_spmm(m, MGGCN_OP_N, H_in, ld_in, d_in, MGGCN_EPI_NONE, P, m->ld_p[l], stream);
     if (rc) return rc;
   }
   return mggcn_gemm(MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, P, m->ld_p[l], W, ldw, 0.f, epi, H_out, ld_out,
@@ -225,7 +256,7 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   if (m->orders[l] == MGGCN_ORDER_GEMM_FIRST) {
     // Eq. 9: T = A^^T Z_G ;  Eq. 10: W_G = H^T T ;  Eq. 11: H_G = T W^T
     const int64_t ldt = padded_ld(d_out);
-    rc = mggcn_spmm(m->g, MGGCN_OP_T, G, ldg, d_out, 0.f, MGGCN_EPI_NONE, tmp, ldt, stream);
+    rc = gathered_spmm(m, MGGCN_OP_T, G, ldg, d_out, MGGCN_EPI_NONE, tmp, ldt, stream);
     if (rc) return rc;
     rc = mggcn_gemm(MGGCN_OP_T, MGGCN_OP_N, d_in, d_out, m->n, H_in, ld_in, tmp, ldt, 0.f, MGGCN_EPI_NONE, W_G,
                     ldwg, gws, m->gemm_ws_bytes, stream);
@@ -242,7 +273,7 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   rc = mggcn_gemm(MGGCN_OP_N, MGGCN_OP_T, m->n, d_in, d_out, G, ldg, W, ldw, 0.f, MGGCN_EPI_NONE, tmp, ldu,
                   nullptr, 0, stream);
   if (rc) return rc;
-  return mggcn_spmm(m->g, MGGCN_OP_T, tmp, ldu, d_in, 0.f, hg_epi, H_G, ldhg, stream);
+  return gathered_spmm(m, MGGCN_OP_T, tmp, ldu, d_in, hg_epi, H_G, ldhg, stream);
 }
 
 int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labels, const float* const* W,

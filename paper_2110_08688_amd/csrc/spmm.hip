@@ -27,9 +27,7 @@
 //   Feature chunks map to blockIdx so that, with 2, 4 or 8 chunks, one chunk always lands on the
 //   same XCDs (workgroups are dealt round-robin over the 8 XCDs): each L2 then caches a
 //   1/n_chunks column slice of X instead of all of it.
-#include "common.h"
-#include "graph.h"
-#include "spmm_device.h"
+#include "spmm_kernel.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -40,7 +38,7 @@
 namespace mggcn {
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kThreads = kSpmmThreads;
 constexpr int kDefaultSegLen = 2048;
 
 // Row-segment tables for `n_panels` column panels.  colidx (host copy) is only needed when
@@ -122,155 +120,40 @@ int pow2_floor(int64_t x) {
   return p;
 }
 
-// Number of column panels: enough that one panel of the gathered operand (at a reference width
-// of 128 floats) is about 24 MB, but no more than the average row length affords -- every panel
-// costs one more read-modify-write of the output (measured: an average row of ~50 entries is
-// slower with 2 panels than with 1, ~490 entries want 8).
-int32_t choose_panels(int32_t n_rows, int32_t n_cols, int64_t nnz) {
-  if (const char* e = std::getenv("MGGCN_PANELS")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 64) return v;
-  }
+// Most column panels a matrix affords: every panel costs one more read-modify-write of the output,
+// which an average row of ~50 entries does not earn back even with 2 panels, while ~490 entries
+// carry 8 (measured).
+int32_t max_panels(int32_t n_rows, int64_t nnz) {
   if (n_rows <= 0 || nnz <= 0) return 1;
-  const int64_t x_ref = (int64_t)n_cols * 512;
-  int64_t by_cache = 1;
-  while (by_cache * (24ll << 20) < x_ref) by_cache <<= 1;
-  const int64_t by_degree = pow2_floor(std::max<int64_t>(1, nnz / n_rows / 32));
-  return (int32_t)std::max<int64_t>(1, std::min<int64_t>(std::min(by_cache, by_degree), 32));
+  return (int32_t)std::min<int64_t>(pow2_floor(std::max<int64_t>(1, nnz / n_rows / 32)), 32);
+}
+
+int pow2_ceil(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+// Panel form for a product whose gathered operand has n_cols rows of F elements of elem_bytes:
+// the smallest power-of-two panel count that brings one panel of the operand down to
+// g->panel_bytes (about 16 MiB measured best on MI355X for both 4- and 2-byte elements: a panel
+// that all wavefronts in flight share then lives in L2 / Infinity Cache), among the forms built.
+const TaskSet* pick_panels(const mggcn_graph* g, const Orientation& o, int32_t F, int elem_bytes, int epilogue) {
+  // the in-place ReLU' mask needs the old Y at every write, which only the single-panel form provides
+  if (o.panelled.empty() || epilogue == MGGCN_EPI_RELU_MASK) return &o.flat;
+  if (g->panels_fixed) return &o.panelled.front();
+  const int64_t bytes = (int64_t)o.n_cols * F * elem_bytes;
+  const int want = pow2_ceil((int)std::min<int64_t>(ceil_div(bytes, std::max<int64_t>(g->panel_bytes, 1)), 1 << 20));
+  if (want <= 1) return &o.flat;
+  const TaskSet* best = &o.panelled.front();
+  for (const TaskSet& ts : o.panelled)
+    if (ts.n_panels <= want) best = &ts;  // ascending panel counts: the largest not above `want`
+  return best;
 }
 
 // ---------------------------------------------------------------------------------------
 // device code
 // ---------------------------------------------------------------------------------------
-
-template <int VW, int LPR, int GPT, int UMAX>
-__global__ __launch_bounds__(kThreads) void spmm_tasks(
-    const Task* __restrict__ tasks, int64_t ntasks, const int32_t* __restrict__ colidx,
-    const float* __restrict__ val, const float* __restrict__ X, uint32_t ldx_bytes, int F, int n_chunks,
-    float beta, int epi, float* __restrict__ Y, int64_t ldy, float* __restrict__ partial,
-    int64_t ldp) {
-  constexpr int TEAM = LPR * GPT;
-  constexpr int TPW = 64 / TEAM;
-  constexpr int U = LPR < UMAX ? LPR : UMAX;
-  static_assert(TEAM <= 64 && TPW >= 1, "team must fit a wavefront");
-
-  const int chunk = (int)(blockIdx.x % (unsigned)n_chunks);
-  const int64_t tb = blockIdx.x / (unsigned)n_chunks;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int team = lane / TEAM, tl = lane % TEAM;
-  const int g = tl / LPR, fl = tl % LPR;
-  const int team_base = team * TEAM;
-  const int64_t t = (tb * (kThreads / 64) + wave) * TPW + team;
-
-  Task task = {0, 0, 0u, -1};
-  const bool has_task = t < ntasks;
-  if (has_task) task = tasks[t];
-  const int len = (int)(task.len_flags & kTaskLenMask);
-
-  // longest and shortest task of this wavefront: uniform loop bounds, so the shuffles below
-  // are executed by all lanes together
-  int maxlen = len, minlen = len;
-#pragma unroll
-  for (int d = TEAM; d < 64; d <<= 1) {
-    maxlen = max(maxlen, __shfl_xor(maxlen, d));
-    minlen = min(minlen, __shfl_xor(minlen, d));
-  }
-  maxlen = __builtin_amdgcn_readfirstlane(maxlen);
-  minlen = __builtin_amdgcn_readfirstlane(minlen);
-
-  const int f0 = chunk * (LPR * VW) + fl * VW;
-  const int nf = min(VW, max(0, F - f0));
-  const bool live = nf > 0;  // this lane covers at least one feature column
-  const char* __restrict__ xbase = reinterpret_cast<const char*>(X + f0);
-  const int32_t* __restrict__ cptr = colidx + task.k0 + tl;
-  const float* __restrict__ vptr = val + task.k0 + tl;
-
-  float acc[VW];
-  float xs[U][VW];
-#pragma unroll
-  for (int i = 0; i < VW; ++i) acc[i] = 0.f;
-#pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int i = 0; i < VW; ++i) xs[u][i] = 0.f;
-
-  int c = 0;
-  float v = 0.f;
-  if (tl < len) {
-    c = __builtin_nontemporal_load(cptr);
-    v = __builtin_nontemporal_load(vptr);
-  }
-  // what the output row holds now, if the epilogue needs it: fetched up front so that its
-  // latency hides behind the gathers
-  const float my_beta = (task.len_flags & kTaskFirst) ? beta : 1.f;
-  const int my_epi = (task.len_flags & kTaskLast) ? epi : (int)MGGCN_EPI_NONE;
-  const bool to_y = has_task && g == 0 && live && task.slot < 0;
-  float old[VW];
-#pragma unroll
-  for (int i = 0; i < VW; ++i) old[i] = 0.f;
-  if (to_y && (my_beta != 0.f || my_epi == MGGCN_EPI_RELU_MASK)) load_row<VW>(Y + (int64_t)task.row * ldy + f0, nf, old);
-  for (int base = 0; base < maxlen; base += TEAM) {
-    int c_next = 0;
-    float v_next = 0.f;
-    if (base + TEAM + tl < len) {
-      c_next = __builtin_nontemporal_load(cptr + base + TEAM);
-      v_next = __builtin_nontemporal_load(vptr + base + TEAM);
-    }
-    // full step: every team of the wavefront still has TEAM entries, nothing to predicate
-    const bool full = base + TEAM <= minlen;
-    const int remaining = maxlen - base;  // uniform
-#pragma unroll 1
-    for (int j0 = 0; j0 < LPR; j0 += U) {
-      if (j0 * GPT >= remaining) break;
-      int cj[U];
-      float vs[U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int src = team_base + (j0 + u) * GPT + g;  // entry handled by my lane group
-        cj[u] = __shfl(c, src);
-        vs[u] = __shfl(v, src);  // 0 beyond the task's end
-      }
-      if (full) {
-        if (live) {
-#pragma unroll
-          for (int u = 0; u < U; ++u)
-            load_vec<VW>(reinterpret_cast<const float*>(xbase + (uint64_t)(uint32_t)cj[u] * ldx_bytes), xs[u]);
-        }
-      } else {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-#pragma unroll
-          for (int i = 0; i < VW; ++i) xs[u][i] = 0.f;
-          if (live && base + (j0 + u) * GPT + g < len)
-            load_vec<VW>(reinterpret_cast<const float*>(xbase + (uint64_t)(uint32_t)cj[u] * ldx_bytes), xs[u]);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int i = 0; i < VW; ++i) acc[i] = fmaf(vs[u], xs[u][i], acc[i]);
-    }
-    c = c_next;
-    v = v_next;
-  }
-
-  // fold the GPT lane groups of the team
-#pragma unroll
-  for (int d = LPR; d < TEAM; d <<= 1)
-#pragma unroll
-    for (int i = 0; i < VW; ++i) acc[i] += __shfl_xor(acc[i], d);
-
-  if (has_task && g == 0 && live) {
-    if (task.slot >= 0)
-      store_out<VW>(partial + (int64_t)task.slot * ldp + f0, nf, acc, 0.f, MGGCN_EPI_NONE, false);
-    else {
-      float r[VW];
-#pragma unroll
-      for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(acc[i], old[i], my_beta, my_epi);
-      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, r, 0.f, MGGCN_EPI_NONE, false);
-    }
-  }
-}
 
 // Rows that were cut: add their partial sums in segment order.
 __global__ __launch_bounds__(kThreads) void spmm_fixup(const FixRow* __restrict__ fix, int64_t nfix,
@@ -291,82 +174,14 @@ __global__ __launch_bounds__(kThreads) void spmm_fixup(const FixRow* __restrict_
   }
 }
 
-struct LaunchArgs {
-  const Task* tasks;
-  int64_t ntasks;
-  const int32_t* colidx;
-  const float* val;
-  const float* X;
-  int64_t ldx;
-  int F, n_chunks;
-  float beta;
-  int epi;
-  float* Y;
-  int64_t ldy;
-  float* partial;
-  int64_t ldp;
-  hipStream_t stream;
-};
-
-template <int VW, int LPR, int GPT>
-int launch_one(const LaunchArgs& a) {
-  constexpr int TPW = 64 / (LPR * GPT);
-  const int64_t teams_per_block = (kThreads / 64) * TPW;
-  const int64_t blocks = ceil_div(a.ntasks, teams_per_block) * a.n_chunks;
-  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "SpMM grid of %lld blocks too large",
-                (long long)blocks);
-  // 4 gathers per lane in flight: 56 VGPRs, 8 wavefronts per SIMD (8 in flight measured no faster)
-  spmm_tasks<VW, LPR, GPT, 4><<<(unsigned)blocks, kThreads, 0, a.stream>>>(
-      a.tasks, a.ntasks, a.colidx, a.val, a.X, (uint32_t)(a.ldx * 4), a.F, a.n_chunks, a.beta, a.epi, a.Y,
-      a.ldy, a.partial, a.ldp);
-  MGGCN_LAUNCH_CHECK();
-  return MGGCN_OK;
-}
-
-template <int VW, int LPR>
-int launch_gpt(int gpt, const LaunchArgs& a) {
-  switch (gpt) {
-    case 1: return launch_one<VW, LPR, 1>(a);
-    case 2: if constexpr (LPR * 2 <= 64) return launch_one<VW, LPR, 2>(a); break;
-    case 4: if constexpr (LPR * 4 <= 64) return launch_one<VW, LPR, 4>(a); break;
-    case 8: if constexpr (LPR * 8 <= 64) return launch_one<VW, LPR, 8>(a); break;
-    case 16: if constexpr (LPR * 16 <= 64) return launch_one<VW, LPR, 16>(a); break;
-    case 32: if constexpr (LPR * 32 <= 64) return launch_one<VW, LPR, 32>(a); break;
-    case 64: if constexpr (LPR * 64 <= 64) return launch_one<VW, LPR, 64>(a); break;
-    default: break;
-  }
-  return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for %d lanes per row x %d groups", LPR, gpt);
-}
-
-template <int VW>
-int launch_lpr(int lpr, int gpt, const LaunchArgs& a) {
-  switch (lpr) {
-    case 1: return launch_gpt<VW, 1>(gpt, a);
-    case 2: return launch_gpt<VW, 2>(gpt, a);
-    case 4: return launch_gpt<VW, 4>(gpt, a);
-    case 8: return launch_gpt<VW, 8>(gpt, a);
-    case 16: return launch_gpt<VW, 16>(gpt, a);
-    case 32: return launch_gpt<VW, 32>(gpt, a);
-    case 64: return launch_gpt<VW, 64>(gpt, a);
-    default: break;
-  }
-  return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for %d lanes per row", lpr);
-}
-
-int launch_any(int vw, int lpr, int gpt, const LaunchArgs& a) {
+int launch_any_f32(int vw, int lpr, int gpt, const LaunchArgs& a) {
   switch (vw) {
-    case 4: return launch_lpr<4>(lpr, gpt, a);
-    case 2: return launch_lpr<2>(lpr, gpt, a);
-    case 1: return launch_lpr<1>(lpr, gpt, a);
+    case 4: return launch_lpr<float, 4>(lpr, gpt, a);
+    case 2: return launch_lpr<float, 2>(lpr, gpt, a);
+    case 1: return launch_lpr<float, 1>(lpr, gpt, a);
     default: break;
   }
   return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for vector width %d", vw);
-}
-
-int pow2_ceil(int x) {
-  int p = 1;
-  while (p < x) p <<= 1;
-  return p;
 }
 
 struct SweepCarve {
@@ -377,8 +192,8 @@ struct SweepCarve {
 };
 
 struct GraphCarve {
-  Task* tasks[2][2];   // [orientation][flat, panelled]
-  FixRow* fix[2][2];
+  std::vector<Task*> tasks[2];   // per orientation: flat form first, then the panel forms
+  std::vector<FixRow*> fix[2];
   SweepCarve sweep[2];
   float* partial;
   int64_t ldp;
@@ -391,12 +206,12 @@ size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* ou
   const Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
   for (int o = 0; o < 2; ++o) {
     if (!os[o]) continue;
-    const TaskSet* sets[2] = {&os[o]->flat, &os[o]->panelled};
-    for (int k = 0; k < 2; ++k) {
-      if (sets[k]->n_panels == 0) continue;
-      gc.tasks[o][k] = c.take<Task>(sets[k]->tasks.size() + 1);
-      gc.fix[o][k] = c.take<FixRow>(sets[k]->fix.size() + 1);
-      slots = std::max(slots, sets[k]->n_slots);
+    std::vector<const TaskSet*> sets = {&os[o]->flat};
+    for (const TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
+    for (const TaskSet* ts : sets) {
+      gc.tasks[o].push_back(c.take<Task>(ts->tasks.size() + 1));
+      gc.fix[o].push_back(c.take<FixRow>(ts->fix.size() + 1));
+      slots = std::max(slots, ts->n_slots);
     }
     const SweepSet& sw = os[o]->sweep;
     if (sw.n_panels > 0) {
@@ -411,7 +226,7 @@ size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* ou
   }
   gc.ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
   gc.partial = c.take<float>((size_t)(slots * gc.ldp) + 64);
-  if (out) *out = gc;
+  if (out) *out = std::move(gc);
   return c.off;
 }
 
@@ -457,6 +272,98 @@ int build_sweep_for(Orientation* o, int32_t n_panels, int32_t rows_per_team, hip
 }  // namespace
 }  // namespace mggcn
 
+namespace mggcn {
+
+int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int32_t F, float beta,
+                    int epilogue, const float* Y, int64_t ldy) {
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
+  MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
+  MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
+  MGGCN_REQUIRE(ldx >= F && ldy >= F, MGGCN_E_INVALID_ARG, "leading dimension (ldx %lld, ldy %lld) < F %d",
+                (long long)ldx, (long long)ldy, F);
+  MGGCN_REQUIRE(ldx < ((int64_t)1 << 30), MGGCN_E_OVERFLOW, "ldx %lld: a row of X must be shorter than 4 GiB",
+                (long long)ldx);
+  MGGCN_REQUIRE(beta == 0.f || beta == 1.f, MGGCN_E_INVALID_ARG, "beta must be 0 or 1");
+  MGGCN_REQUIRE(epilogue == MGGCN_EPI_NONE || epilogue == MGGCN_EPI_RELU || epilogue == MGGCN_EPI_RELU_MASK,
+                MGGCN_E_INVALID_ARG, "unknown epilogue %d", epilogue);
+  MGGCN_REQUIRE(!(epilogue == MGGCN_EPI_RELU_MASK && beta != 0.f), MGGCN_E_INVALID_ARG,
+                "RELU_MASK cannot be combined with beta = 1");
+  MGGCN_REQUIRE(g->bound, MGGCN_E_WORKSPACE, "graph is not bound to a workspace");
+  MGGCN_REQUIRE(F <= g->F_bound, MGGCN_E_WORKSPACE, "F = %d exceeds the bound width %d", F, g->F_bound);
+  const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
+  if (F == 0 || o.n_rows == 0) return MGGCN_OK;
+  MGGCN_REQUIRE(X != nullptr || o.nnz == 0, MGGCN_E_INVALID_ARG, "X is NULL");
+  MGGCN_REQUIRE(Y != nullptr, MGGCN_E_INVALID_ARG, "Y is NULL");
+  return MGGCN_OK;
+}
+
+namespace {
+
+// One product over the first F columns of X / Y with the given task tables.
+int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts, const void* X, int64_t ldx,
+                   int vw, int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream,
+                   SpmmLaunchFn launch) {
+  int lpr = std::min(64, pow2_ceil((int)ceil_div(F, vw)));
+  if (g->chunk_lanes > 0) lpr = std::min(lpr, g->chunk_lanes);
+  const int n_chunks = (int)ceil_div(F, lpr * vw);
+  const int gpt_max = 64 / lpr;
+
+  LaunchArgs a;
+  a.colidx = o.colidx; a.val = o.val; a.X = X; a.ldx = ldx; a.F = F; a.n_chunks = n_chunks;
+  a.beta = beta; a.epi = epilogue; a.Y = Y; a.ldy = ldy; a.partial = g->d_partial; a.ldp = g->ldp;
+  a.stream = as_stream(stream);
+
+  int top = 0;
+  while ((1 << (top + 1)) <= gpt_max) ++top;  // gpt_max = 1 << top
+  for (int32_t p = 0; p < ts.n_panels; ++p) {
+    // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
+    const int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
+    int64_t begin = 0;
+    for (int i = top; i >= 0; --i) {
+      const int64_t end = (i == 0) ? ntasks : ts.cnt_ge[p][i];  // length >= 8 << i  => gpt = 1 << i
+      if (end > begin) {
+        a.tasks = ts.d_tasks + ts.task_begin[p] + begin;
+        a.ntasks = end - begin;
+        const int rc = launch(vw, lpr, 1 << i, a);
+        if (rc) return rc;
+        begin = end;
+      }
+    }
+    const int64_t nfix = ts.fix_begin[(size_t)p + 1] - ts.fix_begin[p];
+    if (nfix > 0) {
+      spmm_fixup<<<(unsigned)nfix, kThreads, 0, a.stream>>>(ts.d_fix + ts.fix_begin[p], nfix, g->d_partial,
+                                                           g->ldp, F, beta, epilogue, Y, ldy);
+      MGGCN_LAUNCH_CHECK();
+    }
+  }
+  return MGGCN_OK;
+}
+
+}  // namespace
+
+int spmm_run(const mggcn_graph* g, const Orientation& o, const void* X, int64_t ldx, int elem_bytes, int vw,
+             int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream, SpmmLaunchFn launch) {
+  const TaskSet& ts = *pick_panels(g, o, F, elem_bytes, epilogue);
+  // A wide operand on a graph with panel forms: when even the largest panel count leaves a panel
+  // of X well above the target size, the feature columns are walked in slices as well, one slice
+  // after the other (each costs one more pass over the entries, 8 bytes each, against a gather
+  // that then stays in the caches: F = 602 on the 233K-vertex graph measured 40 % faster).
+  int64_t slice = F;
+  if (!g->panels_fixed && ts.n_panels > 1) {
+    const int64_t passes = ceil_div((int64_t)o.n_cols * F * elem_bytes, std::max<int64_t>(g->panel_bytes, 1));
+    if (passes > ts.n_panels)  // slices of whole 64-element groups keep every alignment of the full operand
+      slice = (int64_t)align_up((size_t)ceil_div(F, ceil_div(passes, ts.n_panels)), 64);
+  }
+  for (int64_t f = 0; f < F; f += slice) {
+    const int rc = spmm_run_slice(g, o, ts, static_cast<const char*>(X) + f * elem_bytes, ldx, vw,
+                                  (int32_t)std::min<int64_t>(slice, F - f), beta, epilogue, Y + f, ldy, stream, launch);
+    if (rc) return rc;
+  }
+  return MGGCN_OK;
+}
+
+}  // namespace mggcn
+
 using namespace mggcn;
 
 extern "C" {
@@ -490,12 +397,21 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
   g->symmetric = (rowptr_t == nullptr);
   g->seg_len = seg_len;
-  g->panel_min_bytes = n_panels > 1 ? 0 : (24ll << 20);
+  g->panel_bytes = 16ll << 20;
+  g->panels_fixed = n_panels > 1;
   if (const char* e = std::getenv("MGGCN_CHUNK_LANES")) {
     const int v = std::atoi(e);
     if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) g->chunk_lanes = v;
   }
-  if (const char* e = std::getenv("MGGCN_PANEL_MIN_MB")) g->panel_min_bytes = (int64_t)std::atoi(e) << 20;
+  if (const char* e = std::getenv("MGGCN_PANEL_MB")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= (1 << 20)) g->panel_bytes = (int64_t)v << 20;
+  }
+  if (n_panels == 0)
+    if (const char* e = std::getenv("MGGCN_PANELS")) {
+      const int v = std::atoi(e);
+      if (v >= 1 && v <= 64) { n_panels = v; g->panels_fixed = v > 1; }
+    }
 
   auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const int32_t* rp, const int32_t* ci,
                    const float* va) -> int {
@@ -509,13 +425,16 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
     o->nnz = h[nr];
     MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
     build_task_set(&o->flat, nr, nc, h, nullptr, 1, seg_len);
-    const int32_t P = n_panels > 0 ? n_panels : choose_panels(nr, nc, o->nnz);
-    if (P > 1) {
+    const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
+    if (Pmax > 1) {
       // panel cuts need the column indices: one read-back, setup only
       std::vector<int32_t> hc((size_t)o->nnz);
       MGGCN_HIP(hipMemcpyAsync(hc.data(), ci, sizeof(int32_t) * (size_t)o->nnz, hipMemcpyDeviceToHost, s));
       MGGCN_HIP(hipStreamSynchronize(s));
-      build_task_set(&o->panelled, nr, nc, h, hc.data(), P, seg_len);
+      for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
+        o->panelled.emplace_back();
+        build_task_set(&o->panelled.back(), nr, nc, h, hc.data(), P, seg_len);
+      }
     }
     // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
     // and lose the shared panel), so it is built only on request.
@@ -552,10 +471,10 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
   Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
   for (int o = 0; o < 2; ++o) {
     if (!os[o]) continue;
-    TaskSet* sets[2] = {&os[o]->flat, &os[o]->panelled};
-    for (int k = 0; k < 2; ++k) {
+    std::vector<TaskSet*> sets = {&os[o]->flat};
+    for (TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
+    for (size_t k = 0; k < sets.size(); ++k) {
       TaskSet* ts = sets[k];
-      if (ts->n_panels == 0) continue;
       ts->d_tasks = gc.tasks[o][k];
       ts->d_fix = gc.fix[o][k];
       if (!ts->tasks.empty())
@@ -620,51 +539,30 @@ int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
   MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
-  const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
+  const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes;
   if (o.sweep.n_panels > 0 && (g->sweep_forced || big)) return 1;  // sweep form: one launch
-  return (o.panelled.n_panels > 1 && big) ? o.panelled.n_panels : 1;
+  return pick_panels(g, o, F, (int)sizeof(float), MGGCN_EPI_NONE)->n_panels;
 }
 
 int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_t F, float beta,
                int epilogue, float* Y, int64_t ldy, void* stream) {
-  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
-  MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
-  MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
-  MGGCN_REQUIRE(ldx >= F && ldy >= F, MGGCN_E_INVALID_ARG, "leading dimension (ldx %lld, ldy %lld) < F %d",
-                (long long)ldx, (long long)ldy, F);
-  MGGCN_REQUIRE(ldx < ((int64_t)1 << 30), MGGCN_E_OVERFLOW, "ldx %lld: a row of X must be shorter than 4 GiB",
-                (long long)ldx);
-  MGGCN_REQUIRE(beta == 0.f || beta == 1.f, MGGCN_E_INVALID_ARG, "beta must be 0 or 1");
-  MGGCN_REQUIRE(epilogue == MGGCN_EPI_NONE || epilogue == MGGCN_EPI_RELU || epilogue == MGGCN_EPI_RELU_MASK,
-                MGGCN_E_INVALID_ARG, "unknown epilogue %d", epilogue);
-  MGGCN_REQUIRE(!(epilogue == MGGCN_EPI_RELU_MASK && beta != 0.f), MGGCN_E_INVALID_ARG,
-                "RELU_MASK cannot be combined with beta = 1");
-  MGGCN_REQUIRE(g->bound, MGGCN_E_WORKSPACE, "graph is not bound to a workspace");
-  MGGCN_REQUIRE(F <= g->F_bound, MGGCN_E_WORKSPACE, "F = %d exceeds the bound width %d", F, g->F_bound);
+  int rc = spmm_check_args(g, op, X, ldx, F, beta, epilogue, Y, ldy);
+  if (rc) return rc;
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
   if (F == 0 || o.n_rows == 0) return MGGCN_OK;
-  MGGCN_REQUIRE(X != nullptr || o.nnz == 0, MGGCN_E_INVALID_ARG, "X is NULL");
-  MGGCN_REQUIRE(Y != nullptr, MGGCN_E_INVALID_ARG, "Y is NULL");
 
   int vw = 1;
   if (aligned(X, 16) && aligned(Y, 16) && ldx % 4 == 0 && ldy % 4 == 0) vw = 4;
   else if (aligned(X, 8) && aligned(Y, 8) && ldx % 2 == 0 && ldy % 2 == 0) vw = 2;
-  int lpr = std::min(64, pow2_ceil((int)ceil_div(F, vw)));
-  if (g->chunk_lanes > 0) lpr = std::min(lpr, g->chunk_lanes);
-  const int n_chunks = (int)ceil_div(F, lpr * vw);
-  const int gpt_max = 64 / lpr;
-
-  // Column panels pay when the gathered operand is much larger than the caches; the in-place
-  // ReLU' mask needs the old Y at every write, which only the single-panel form provides.
-  const bool use_panels = o.panelled.n_panels > 1 && epilogue != MGGCN_EPI_RELU_MASK &&
-                          (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes;
-  const TaskSet& ts = use_panels ? o.panelled : o.flat;
 
   // Sweep form (one launch, every row of Y written once) where it was built and X is large.
+  int lpr = std::min(64, pow2_ceil((int)ceil_div(F, vw)));
+  if (g->chunk_lanes > 0) lpr = std::min(lpr, g->chunk_lanes);
   if (o.sweep.n_panels > 0 && vw == 4 && lpr >= 4 &&
-      (g->sweep_forced || (int64_t)o.n_cols * F * (int64_t)sizeof(float) >= g->panel_min_bytes)) {
+      (g->sweep_forced || (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes)) {
+    const int n_chunks = (int)ceil_div(F, lpr * vw);
     const SweepSet& sw = o.sweep;
-    const int rc = launch_sweep(sw, X, ldx, F, lpr, n_chunks, beta, epilogue, Y, ldy, g->d_partial, g->ldp, stream);
+    rc = launch_sweep(sw, X, ldx, F, lpr, n_chunks, beta, epilogue, Y, ldy, g->d_partial, g->ldp, stream);
     if (rc == MGGCN_OK) {
       if (!sw.fix.empty()) {
         spmm_fixup<<<(unsigned)sw.fix.size(), kThreads, 0, as_stream(stream)>>>(
@@ -675,36 +573,7 @@ int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_
     }
     if (rc != MGGCN_E_UNSUPPORTED) return rc;
   }
-
-  LaunchArgs a;
-  a.colidx = o.colidx; a.val = o.val; a.X = X; a.ldx = ldx; a.F = F; a.n_chunks = n_chunks;
-  a.beta = beta; a.epi = epilogue; a.Y = Y; a.ldy = ldy; a.partial = g->d_partial; a.ldp = g->ldp;
-  a.stream = as_stream(stream);
-
-  int top = 0;
-  while ((1 << (top + 1)) <= gpt_max) ++top;  // gpt_max = 1 << top
-  for (int32_t p = 0; p < ts.n_panels; ++p) {
-    // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
-    const int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
-    int64_t begin = 0;
-    for (int i = top; i >= 0; --i) {
-      const int64_t end = (i == 0) ? ntasks : ts.cnt_ge[p][i];  // length >= 8 << i  => gpt = 1 << i
-      if (end > begin) {
-        a.tasks = ts.d_tasks + ts.task_begin[p] + begin;
-        a.ntasks = end - begin;
-        const int rc = launch_any(vw, lpr, 1 << i, a);
-        if (rc) return rc;
-        begin = end;
-      }
-    }
-    const int64_t nfix = ts.fix_begin[(size_t)p + 1] - ts.fix_begin[p];
-    if (nfix > 0) {
-      spmm_fixup<<<(unsigned)nfix, kThreads, 0, a.stream>>>(ts.d_fix + ts.fix_begin[p], nfix, g->d_partial,
-                                                           g->ldp, F, beta, epilogue, Y, ldy);
-      MGGCN_LAUNCH_CHECK();
-    }
-  }
-  return MGGCN_OK;
+  return spmm_run(g, o, X, ldx, (int)sizeof(float), vw, F, beta, epilogue, Y, ldy, stream, launch_any_f32);
 }
 
 }  // extern "C"

@@ -11,9 +11,12 @@ namespace mggcn {
 template <int VW>
 __device__ inline void load_row(const float* __restrict__ p, int nf, float (&x)[VW]) {
   if (nf == VW) {
-    if constexpr (VW == 4) {
-      const float4 t = *reinterpret_cast<const float4*>(p);
-      x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+    if constexpr (VW % 4 == 0) {
+#pragma unroll
+      for (int q = 0; q < VW / 4; ++q) {
+        const float4 t = reinterpret_cast<const float4*>(p)[q];
+        x[4 * q] = t.x; x[4 * q + 1] = t.y; x[4 * q + 2] = t.z; x[4 * q + 3] = t.w;
+      }
     } else if constexpr (VW == 2) {
       const float2 t = *reinterpret_cast<const float2*>(p);
       x[0] = t.x; x[1] = t.y;
@@ -50,8 +53,10 @@ __device__ inline void store_out(float* __restrict__ dst, int nf, const float (&
     for (int i = 0; i < VW; ++i) r[i] = a[i];
   }
   if (nf == VW) {
-    if constexpr (VW == 4) {
-      *reinterpret_cast<float4*>(dst) = make_float4(r[0], r[1], r[2], r[3]);
+    if constexpr (VW % 4 == 0) {
+#pragma unroll
+      for (int q = 0; q < VW / 4; ++q)
+        reinterpret_cast<float4*>(dst)[q] = make_float4(r[4 * q], r[4 * q + 1], r[4 * q + 2], r[4 * q + 3]);
     } else if constexpr (VW == 2) {
       *reinterpret_cast<float2*>(dst) = make_float2(r[0], r[1]);
     } else {
@@ -69,6 +74,7 @@ __device__ inline void store_out(float* __restrict__ dst, int nf, const float (&
 // feed accumulator components that are never stored.
 template <int VW>
 __device__ inline void load_vec(const float* __restrict__ p, float (&x)[VW]) {
+  static_assert(VW == 4 || VW == 2 || VW == 1, "fp32 gathers are 16, 8 or 4 bytes per lane");
   if constexpr (VW == 4) {
     const float4 t = *reinterpret_cast<const float4*>(p);
     x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;

@@ -119,6 +119,65 @@ def test_medium_epoch(medium, ref):
         assert e.max() <= 1e-4
 
 
+@pytest.mark.parametrize("F,ld", [(128, 128), (41, 48)])
+def test_medium_spmm_bf16_all_rows(medium, ref, F, ld):
+    """bfloat16 copy of the gathered operand (extension): same per-row bound against the oracle fed
+    the same rounded values; the conversion itself is bit exact."""
+    import torch
+
+    m = medium
+    mg, dev, n = m["mg"], m["dev"], m["n"]
+    say(f"[medium spmm bf16] F={F} ld={ld}")
+    Xp = wl.normal_f32(4343, F, (n, ld))
+    Xb = torch.empty((n, ld), dtype=torch.int16, device=dev)
+    mg.mggcn_f32_to_bf16(torch.from_numpy(Xp).to(dev)[:, :F], dst=Xb[:, :F])
+    codes, Xq = ref.bf16_round(np.ascontiguousarray(Xp[:, :F]))
+    assert np.array_equal(Xb[:, :F].cpu().numpy().view(np.uint16), codes)
+    Yd = torch.zeros((n, ld), device=dev)
+    mg.mggcn_spmm_bf16(m["graph"], mg.OP_N, Xb[:, :F], Y=Yd[:, :F])
+    got = Yd.cpu().numpy()
+    want = ref.spmm(ref.OP_N, n, n, m["rp"], m["ci"], m["rv"].astype(np.float32).astype(np.float64),
+                    Xq.astype(np.float64))
+    e = row_err(got[:, :F], want)
+    say(f"[medium spmm bf16] max row rel err {e.max():.3e}")
+    assert e.max() <= 1e-4
+    assert np.all(got[:, F:] == 0)
+
+
+def test_medium_epoch_bf16(medium, ref):
+    """Epoch with MODEL_GATHER_BF16 at full size: the oracle's bfloat16-gather epoch, handed the device's
+    ReLU' decisions and SpMM operands, must give the same loss and weight gradients; the operands
+    themselves must be the roundings of (nearly) the oracle's own values."""
+    import torch
+
+    from test_gpu_bf16 import assert_operands_are_roundings, manual_epoch
+
+    m = medium
+    mg, dev, n, cfg = m["mg"], m["dev"], m["n"], m["cfg"]
+    X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
+    model = mg.Model(m["graph"], cfg.dims, flags=mg.MODEL_GATHER_BF16)
+    Xd, Wd, ld = torch.from_numpy(X).to(dev), [torch.from_numpy(w).to(dev) for w in Ws], torch.from_numpy(labels).to(dev)
+    loss, WG = mg.mggcn_epoch(model, Xd, ld, Wd)
+    mloss, mWG, masks, fwd, bwd = manual_epoch(mg, model, Xd, ld, Wd)
+    assert loss.item() == mloss.item()
+    for a, b in zip(WG, mWG):
+        assert torch.equal(a, b), "layer-by-layer epoch differs from mggcn_epoch"
+    say(f"[medium epoch bf16] gpu loss {loss.item():.7f}; running the fp64 oracle epoch on the host ...")
+    t0 = time.time()
+    rl, rWG, own_f, own_b = ref.epoch_bf16(n, m["rp"], m["ci"], m["rv"].astype(np.float32).astype(np.float64),
+                                           X.astype(np.float64), labels, [w.astype(np.float64) for w in Ws],
+                                           relu_masks=masks, fwd_codes=fwd, bwd_codes=bwd)
+    say(f"[medium epoch bf16] oracle {time.time() - t0:.1f}s loss {rl:.7f}")
+    assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
+    for l, (a, b) in enumerate(zip(WG, rWG)):
+        e = row_err(a.cpu().numpy(), b)
+        say(f"[medium epoch bf16] W_G[{l}] max row rel err {e.max():.3e}")
+        assert e.max() <= 1e-4
+        f1 = assert_operands_are_roundings(fwd[l], own_f[l], f"fwd operand {l}")
+        f2 = assert_operands_are_roundings(bwd[l], own_b[l], f"bwd operand {l}")
+        say(f"[medium epoch bf16] layer {l}: operand entries rounded to the other neighbour: fwd {f1:.2e}, bwd {f2:.2e}")
+
+
 # ----------------------------------------------------------------------------------------------
 # Products-shaped "large" configuration: 2,449,029 vertices, ~126M entries, 100 -> 256 -> 256 -> 47
 # (first layer runs SpMM first, the other two GeMM first)
