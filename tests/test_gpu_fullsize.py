@@ -338,6 +338,34 @@ def test_row_block_spmm_sampled_rows(ref):
         worst = max(worst, err)
     say(f"[block] {len(rows)} sampled rows, max row rel err {worst:.3e}")
     assert worst <= 1e-4
+    # the same product with a bfloat16 copy of X: it differs from the fp32 one by the rounding of X
+    # only (at most 2^-8 of |A^||X| per row); both are timed here because this is the configuration
+    # whose 111 M gathered rows no cache holds
+    Xb = torch.empty((nc, F), dtype=torch.int16, device=dev)
+    mg.mggcn_f32_to_bf16(Xd, dst=Xb)
+    Yb = torch.empty_like(Yd)
+    t32, t16 = [], []
+    for _ in range(3):
+        a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        a.record()
+        mg.mggcn_spmm(graph, mg.OP_N, Xd, Y=Yd)
+        b.record()
+        mg.mggcn_spmm_bf16(graph, mg.OP_N, Xb, Y=Yb)
+        c.record()
+        torch.cuda.synchronize()
+        t32.append(a.elapsed_time(b))
+        t16.append(b.elapsed_time(c))
+    nnz = len(ci)
+    beff = 8 * nnz + 4 * (nr + 1) + 4 * F * nnz + 4 * F * nr
+    say(f"[block] spmm F={F}: fp32 operand {min(t32):.2f} ms = {beff / min(t32) / 1e6:.0f} GB/s effective "
+        f"({100 * beff / min(t32) / 1e6 / 8000:.1f} % of 8 TB/s); bfloat16 operand {min(t16):.2f} ms")
+    Ab = mg.mggcn_spmm(graph, mg.OP_N, Xd.abs_())     # |A^||X| (values of A^ are positive); Xd is regenerated below
+    diff = (Yb - Yd).abs().max(dim=1).values
+    assert bool((diff <= (2.0 ** -8 + 1e-5) * Ab.max(dim=1).values.clamp_min(1e-30)).all())
+    del Xb, Yb, Ab
+    for r0 in range(0, nc, chunk):
+        r1 = min(nc, r0 + chunk)
+        Xd[r0:r1].copy_(torch.from_numpy(wl.normal_f32(cfg.seed + 0x100, 0, (r1 - r0, F), first=r0 * F)))
     # transposed product on the same block (gradient of the dense operand): adjoint identity on a
     # sampled pair, <A X, G> = <X, A^T G>, with G supported on the sampled rows only
     Gd = torch.zeros((nr, F), dtype=torch.float32, device=dev)
