@@ -146,8 +146,9 @@ int mggcn_graph_destroy(mggcn_graph* g);
  * SYNCHRONISES, invalidates the binding: call mggcn_graph_bind afterwards.  Column count must
  * fit 28 bits. */
 int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_team, void* stream);
-/* Number of column-panel passes a plain (epilogue NONE or RELU) SpMM of width F with the given
- * op makes on this graph (1 = single pass), or a negative status. */
+/* Number of passes over the entries a plain (epilogue NONE or RELU) fp32 SpMM of width F with
+ * the given op makes on this graph: column panels x feature slices (1 = single pass), or a
+ * negative status. */
 int mggcn_graph_panels(const mggcn_graph* g, int op /*mggcn_op*/, int32_t F);
 
 /* SpMM (Eq. 6 forward, Eq. 9 backward):   Y = epilogue( op(A^) X + beta Y )

@@ -341,19 +341,32 @@ int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts
 
 }  // namespace
 
-int spmm_run(const mggcn_graph* g, const Orientation& o, const void* X, int64_t ldx, int elem_bytes, int vw,
-             int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream, SpmmLaunchFn launch) {
+// Panel form and feature-slice width for one product.
+// A wide operand on a graph with panel forms: when even the largest panel count leaves a panel
+// of X well above the target size, the feature columns are walked in slices as well, one slice
+// after the other (each costs one more pass over the entries, 8 bytes each, against a gather
+// that then stays in the caches: F = 602 on the 233K-vertex graph measured 40 % faster).
+const TaskSet& plan_passes(const mggcn_graph* g, const Orientation& o, int32_t F, int elem_bytes, int epilogue,
+                           int64_t* slice_out) {
   const TaskSet& ts = *pick_panels(g, o, F, elem_bytes, epilogue);
-  // A wide operand on a graph with panel forms: when even the largest panel count leaves a panel
-  // of X well above the target size, the feature columns are walked in slices as well, one slice
-  // after the other (each costs one more pass over the entries, 8 bytes each, against a gather
-  // that then stays in the caches: F = 602 on the 233K-vertex graph measured 40 % faster).
-  int64_t slice = F;
+  int64_t slice = std::max(F, 1);
   if (!g->panels_fixed && ts.n_panels > 1) {
     const int64_t passes = ceil_div((int64_t)o.n_cols * F * elem_bytes, std::max<int64_t>(g->panel_bytes, 1));
-    if (passes > ts.n_panels)  // slices of whole 64-element groups keep every alignment of the full operand
+    if (passes > ts.n_panels) {
+      // slices of whole 64-element groups keep every alignment of the full operand; a slice narrower
+      // than 512 bytes of a row gathers too little per entry to pay for re-reading the entries
       slice = (int64_t)align_up((size_t)ceil_div(F, ceil_div(passes, ts.n_panels)), 64);
+      slice = std::max<int64_t>(slice, 512 / elem_bytes);
+    }
   }
+  *slice_out = slice;
+  return ts;
+}
+
+int spmm_run(const mggcn_graph* g, const Orientation& o, const void* X, int64_t ldx, int elem_bytes, int vw,
+             int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream, SpmmLaunchFn launch) {
+  int64_t slice = F;
+  const TaskSet& ts = plan_passes(g, o, F, elem_bytes, epilogue, &slice);
   for (int64_t f = 0; f < F; f += slice) {
     const int rc = spmm_run_slice(g, o, ts, static_cast<const char*>(X) + f * elem_bytes, ldx, vw,
                                   (int32_t)std::min<int64_t>(slice, F - f), beta, epilogue, Y + f, ldy, stream, launch);
@@ -541,7 +554,9 @@ int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
   const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes;
   if (o.sweep.n_panels > 0 && (g->sweep_forced || big)) return 1;  // sweep form: one launch
-  return pick_panels(g, o, F, (int)sizeof(float), MGGCN_EPI_NONE)->n_panels;
+  int64_t slice = F;
+  const TaskSet& ts = plan_passes(g, o, F, (int)sizeof(float), MGGCN_EPI_NONE, &slice);
+  return (int)(ts.n_panels * ceil_div(std::max(F, 1), slice));
 }
 
 int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_t F, float beta,

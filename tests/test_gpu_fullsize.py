@@ -379,3 +379,96 @@ def test_row_block_spmm_sampled_rows(ref):
         rhs += float((Xd[r0:r1].double() * Td[r0:r1].double()).sum().item())
     say(f"[block] adjoint identity {lhs:.9e} vs {rhs:.9e}")
     assert abs(lhs - rhs) <= 1e-5 * abs(lhs)
+
+
+# ----------------------------------------------------------------------------------------------
+# Proteins-shaped graph (Table 1 of the paper: 8.74M vertices, 1.3B entries, 128 -> 256 -> 256 -> 256),
+# the largest graph the paper trains on a single GPU.  The oracle is still affordable for one
+# product over all rows; the first layer is checked on a row sample; the whole epoch is only run.
+# ----------------------------------------------------------------------------------------------
+
+def test_proteins_shaped_spmm_and_first_layer(ref):
+    import torch
+
+    import paper_2110_08688_amd as mg
+
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS["proteins"]
+    t0 = time.time()
+    g = cfg.graph()
+    n = g.n_rows
+    say(f"[proteins] generated n={n} nnz={g.nnz} max degree {int(np.diff(g.rowptr).max())} in {time.time() - t0:.1f}s")
+    rowptr, colidx, val = mg.mggcn_csr_normalize(n, n, torch.from_numpy(g.rowptr).to(dev),
+                                                 torch.from_numpy(g.colidx).to(dev))
+    t0 = time.time()
+    rp, ci, rv = ref.csr_normalize(n, n, g.rowptr, g.colidx)
+    del g
+    say(f"[proteins] oracle normalise {time.time() - t0:.1f}s, entries with self-loops {len(ci)}")
+    assert np.array_equal(rowptr.cpu().numpy(), rp) and np.array_equal(colidx.cpu().numpy(), ci)
+    v32 = rv.astype(np.float32)
+    assert np.array_equal(val.cpu().numpy().view(np.int32), v32.view(np.int32))
+    rv = v32.astype(np.float64)
+    del v32
+    t0 = time.time()
+    graph = mg.Graph(n, n, rowptr, colidx, val, F_max=256)
+    say(f"[proteins] task tables in {time.time() - t0:.1f}s, panels at F=128/256: {graph.panels(128)}/{graph.panels(256)}")
+    F = cfg.dims[0]
+    X = cfg.features(n)
+    Xd = torch.from_numpy(X).to(dev)
+    Yd = mg.mggcn_spmm(graph, mg.OP_N, Xd)
+    t0 = time.time()
+    want = ref.spmm(ref.OP_N, n, n, rp, ci, rv, X.astype(np.float64))
+    e = row_err(Yd.cpu().numpy(), want)
+    say(f"[proteins] spmm F={F} over all rows: oracle {time.time() - t0:.1f}s, max row rel err {e.max():.3e}")
+    assert e.max() <= 1e-4
+    # timing, fp32 and bfloat16 operand
+    Xb = mg.mggcn_f32_to_bf16(Xd)
+    Yb = torch.empty_like(Yd)
+    t32, t16 = [], []
+    for _ in range(3):
+        a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        a.record()
+        mg.mggcn_spmm(graph, mg.OP_N, Xd, Y=Yd)
+        b.record()
+        mg.mggcn_spmm_bf16(graph, mg.OP_N, Xb, Y=Yb)
+        c.record()
+        torch.cuda.synchronize()
+        t32.append(a.elapsed_time(b))
+        t16.append(b.elapsed_time(c))
+    nnz = len(ci)
+    beff = 8 * nnz + 4 * (n + 1) + 4 * F * nnz + 4 * F * n
+    say(f"[proteins] spmm F={F}: fp32 operand {min(t32):.2f} ms = {beff / min(t32) / 1e6:.0f} GB/s effective "
+        f"({100 * beff / min(t32) / 1e6 / 8000:.1f} % of 8 TB/s); bfloat16 operand {min(t16):.2f} ms")
+    _, Xq = ref.bf16_round(X)
+    del X
+    rows = np.unique(np.random.default_rng(9).integers(0, n, 2048))
+    gotb = Yb[torch.from_numpy(rows).to(dev)].cpu().numpy()
+    for j, i in enumerate(rows):  # bfloat16 product on sampled rows, by the definition
+        k0, k1 = rp[i], rp[i + 1]
+        acc = rv[k0:k1] @ Xq[ci[k0:k1]].astype(np.float64)
+        assert np.abs(gotb[j] - acc).max() <= 1e-4 * np.abs(acc).max()
+    del Xq, Xb, Yb
+    # first layer (SpMM first: 128 < 256) on a row sample: relu((A^ X) W), with A^ X from the oracle
+    Ws = cfg.weights()
+    model = mg.Model(graph, cfg.dims)
+    assert model.order(0) == mg.ORDER_SPMM_FIRST and model.order(1) == mg.ORDER_GEMM_FIRST
+    Wd = [torch.from_numpy(w).to(dev) for w in Ws]
+    H1 = mg.mggcn_layer_fwd(model, 0, Xd, Wd[0], relu=True)
+    rows = np.unique(np.random.default_rng(10).integers(0, n, 100_000))
+    ref_rows = np.maximum(want[rows] @ Ws[0].astype(np.float64), 0.0)
+    e = row_err(H1[torch.from_numpy(rows).to(dev)].cpu().numpy(), ref_rows)
+    say(f"[proteins] layer 0 forward on {len(rows)} sampled rows: max row rel err {e.max():.3e}")
+    assert e.max() <= 2e-4  # ReLU may flip entries at |z| ~ 1e-7
+    del want, H1
+    # the whole epoch at this size: run and timed; its loss must sit just above ln(256) (small random
+    # weights, uniform labels) and repeat bit for bit.  No oracle epoch at this size (~10 TFLOP of fp64 GeMM).
+    labels = torch.from_numpy(cfg.labels(n)).to(dev)
+    loss, WG = mg.mggcn_epoch(model, Xd, labels, Wd)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    loss2, WG2 = mg.mggcn_epoch(model, Xd, labels, Wd)
+    torch.cuda.synchronize()
+    say(f"[proteins] epoch {1e3 * (time.time() - t0):.1f} ms, loss {loss.item():.6f} (ln 256 = {np.log(256.0):.6f})")
+    assert loss.item() == loss2.item() and all(torch.equal(a, b) for a, b in zip(WG, WG2))
+    assert np.log(256.0) <= loss.item() <= np.log(256.0) + 0.05
+    assert all(bool(torch.isfinite(w).all()) for w in WG)

@@ -186,6 +186,10 @@ CONFIGS = {
         "block", 3, (128, 256),
         lambda s: row_block(13_900_000, 111_000_000, 200e6 - 13.9e6, 2.5, 20000.0, 0.909, s),
     ),
+    # Proteins-shaped (the largest graph the paper trains on one GPU): 8.74M vertices, ~1.3B directed
+    # entries (average degree ~150), 128-256-256-256.  Beyond the benchmark's named configurations;
+    # needs ~30 GB of host memory to generate
+    "proteins": Config("proteins", 5, (128, 256, 256, 256), lambda s: chung_lu(8_740_000, 1.3e9, 2.3, 20000.0, s)),
     # skewed R-MAT graph for the feature-width sweep
     "rmat": Config("rmat", 4, (128, 128), lambda s: rmat(22, 32_000_000, 0.57, 0.19, 0.19, s)),
 }
