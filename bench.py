@@ -28,7 +28,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 
 # HBM bytes per launch of the F=128 SpMM measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # filled in from profiles/ once measured; None = not measured.
-MEASURED_TRAFFIC_BYTES = 2_910_116_677  # per panel launch; profiles/spmm_medium_F128_pmc.md
+MEASURED_TRAFFIC_BYTES = 2_924_326_743  # per panel launch; profiles/spmm_medium_F128_pmc.md
 
 
 def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--profile-spmm", type=int, default=0, metavar="N",
                     help="counter-collection mode: N forward SpMM calls at the epoch's widest width plus one "
                          "1 GiB device copy of known size (calibration), then exit")
+    ap.add_argument("--profile-gemm", type=int, default=0, metavar="N",
+                    help="counter-collection mode: N calls of the first layer's forward GeMM (H W with the padded "
+                         "leading dimension the epoch uses), then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -141,6 +144,15 @@ def main() -> int:
         print(json.dumps({"mode": "profile-spmm", "calls": args.profile_spmm, "F": F, "n": n, "nnz": nnz,
                           "passes": graph.panels(F), "algorithmic_bytes_per_call": spmm_bytes(nnz, n, F),
                           "copy_bytes_each_way": 4 << 28}))
+        return 0
+
+    if args.profile_gemm > 0:
+        out = torch.empty((n, (dims[1] + 15) // 16 * 16), device=dev)[:, :dims[1]]
+        for _ in range(args.profile_gemm):
+            mg.mggcn_gemm(mg.OP_N, mg.OP_N, X, Ws[0], Cm=out)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "profile-gemm", "calls": args.profile_gemm, "M": n, "N": dims[1], "K": dims[0],
+                          "lda": int(X.stride(0)), "flop_per_call": 2 * n * dims[0] * dims[1]}))
         return 0
 
     WG = [torch.empty_like(w) for w in Ws]
