@@ -26,9 +26,12 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
-# HBM bytes per launch of the F=128 SpMM measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# filled in from profiles/ once measured; None = not measured.
-MEASURED_TRAFFIC_BYTES = 2_924_326_743  # per panel launch; profiles/spmm_medium_F128_pmc.md
+# HBM bytes per launch of the dominant SpMM kernel measured with rocprofv3 --pmc (FETCH_SIZE,
+# WRITE_SIZE, calibrated against a copy of known size); configurations not listed: not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "medium": 2_924_326_743,    # F=128, per panel launch; profiles/spmm_medium_F128_pmc.md
+    "large": 129_270_000_000,   # F=256, one launch per call; profiles/spmm_large_pmc.md
+}
 
 
 def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
@@ -83,6 +86,8 @@ def main() -> int:
     ap.add_argument("--profile-spmm", type=int, default=0, metavar="N",
                     help="counter-collection mode: N forward SpMM calls at the epoch's widest width plus one "
                          "1 GiB device copy of known size (calibration), then exit")
+    ap.add_argument("--profile-width", type=int, default=0, metavar="F",
+                    help="with --profile-spmm: the feature width to run at (default: the epoch's widest SpMM)")
     ap.add_argument("--profile-gemm", type=int, default=0, metavar="N",
                     help="counter-collection mode: N calls of the first layer's forward GeMM (H W with the padded "
                          "leading dimension the epoch uses), then exit")
@@ -132,9 +137,10 @@ def main() -> int:
     setup_s = time.time() - t0
 
     if args.profile_spmm > 0:
-        F = max(dims[l] if model.order(l) == mg.ORDER_SPMM_FIRST else dims[l + 1] for l in range(L))
-        src = torch.randn((n, F), device=dev)
-        dst = torch.empty((n, F), device=dev)
+        F = args.profile_width or max(dims[l] if model.order(l) == mg.ORDER_SPMM_FIRST else dims[l + 1] for l in range(L))
+        ld = (F + 15) // 16 * 16
+        src = torch.randn((n, ld), device=dev)[:, :F]
+        dst = torch.empty((n, ld), device=dev)[:, :F]
         for _ in range(args.profile_spmm):
             mg.mggcn_spmm(graph, mg.OP_N, src, epilogue=mg.EPI_RELU, Y=dst)
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)  # 1 GiB
@@ -268,7 +274,7 @@ def main() -> int:
                   f"+ the small row fix-up launches)",
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
-        "traffic": MEASURED_TRAFFIC_BYTES if args.config == "medium" else None,
+        "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
         "launches_per_call": P,
         "algorithmic_bytes_per_launch": dom_bytes // P,
         "avg_launch_ms": round(dom_ms / P, 4),
