@@ -275,6 +275,8 @@ def main() -> int:
         "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBPS, 4),
         "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+        "frac_by_measured_traffic": (round(MEASURED_TRAFFIC_BYTES[args.config] / (dom_ms / P * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+                                     if args.config in MEASURED_TRAFFIC_BYTES else None),
         "launches_per_call": P,
         "algorithmic_bytes_per_launch": dom_bytes // P,
         "avg_launch_ms": round(dom_ms / P, 4),
