@@ -381,6 +381,19 @@ def test_epoch_bf16_with_cached_input(mg, dev, ref):
     run_epoch_case(mg, dev, ref, g, (50, 24, 7), None, 11, cached=True)
 
 
+def test_epoch_bf16_random_cases(mg, dev, ref):
+    """Seeded random models with bfloat16 gathers: depths 1-3, mixed widths, forced orders."""
+    rng = np.random.default_rng(78)
+    for case in range(8):
+        n = int(rng.integers(200, 1500))
+        L = int(rng.integers(1, 4))
+        dims = tuple(int(x) for x in rng.choice([8, 16, 33, 41, 64, 100], size=L + 1))
+        forced = [None, mg.ORDER_GEMM_FIRST, mg.ORDER_SPMM_FIRST][int(rng.integers(0, 3))]
+        say(f"[epoch bf16 random {case}] n={n} dims={dims} forced={forced}")
+        g = wl.chung_lu(n, float(n * rng.integers(5, 40)), 2.2, float(n) / 2, 2000 + case)
+        run_epoch_case(mg, dev, ref, g, dims, None if forced is None else [forced] * L, 100 + case)
+
+
 def test_model_bf16_flag_errors(mg, dev, ref):
     g = wl.CONFIGS["tiny"].graph()
     rp, ci, val = normalized(ref, g)

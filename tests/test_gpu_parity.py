@@ -552,6 +552,43 @@ def test_epoch(mg, dev, ref, cfg_name, dims, orders):
         assert model.order(l) == want_order
 
 
+def test_epoch_random_cases(mg, dev, ref):
+    """Seeded random models on small random graphs: depth 1-4, widths 1-150 (so both orders of the
+    rule, ties, ragged tiles and single-column layers occur), forced orders, both normalisations."""
+    rng = np.random.default_rng(77)
+    for case in range(14):
+        n = int(rng.integers(40, 1500))
+        L = int(rng.integers(1, 5))
+        dims = tuple(int(x) for x in rng.choice([1, 2, 7, 16, 33, 41, 64, 100, 150], size=L + 1))
+        forced = [None, "gemm", "spmm"][int(rng.integers(0, 3))]
+        mean = bool(rng.integers(0, 2))
+        say(f"[epoch random {case}] n={n} dims={dims} forced={forced} mean={mean}")
+        g = wl.chung_lu(n, float(n * rng.integers(3, 40)), 2.2, float(n) / 2, 1000 + case)
+        mode = ref.NORM_MEAN_IN if mean else ref.NORM_SYM
+        rp, ci, val = normalized(ref, g, mode=mode)
+        X = wl.normal_f32(case, 30, (n, dims[0]))
+        Ws = [wl.glorot_f32(case, 40 + l, dims[l], dims[l + 1]) for l in range(L)]
+        labels = wl.labels_i32(case, 50, n, dims[-1])
+        d = [to_dev(a, dev) for a in (rp, ci, val)]
+        t = mg.mggcn_csr_transpose(n, n, *d) if mean else None   # mean normalisation is not symmetric
+        G = mg.Graph(n, n, *d, transpose=t, F_max=max(dims))
+        ords = None if forced is None else [mg.ORDER_GEMM_FIRST if forced == "gemm" else mg.ORDER_SPMM_FIRST] * L
+        model = mg.Model(G, dims, orders=ords)
+        Xd, Wd = to_dev(X, dev), [to_dev(w, dev) for w in Ws]
+        loss, WG = mg.mggcn_epoch(model, Xd, to_dev(labels, dev), Wd)
+        masks = gpu_relu_decisions(mg, model, Xd, Wd)
+        r_ords = [ref.SPMM_FIRST if model.order(l) == mg.ORDER_SPMM_FIRST else ref.GEMM_FIRST for l in range(L)]
+        rl, rWG, _ = ref.epoch(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
+                               [w.astype(np.float64) for w in Ws], orders=r_ords, relu_masks=masks)
+        assert abs(loss.item() - rl) <= 1e-5 * max(abs(rl), 1e-3), (case, loss.item(), rl)
+        for l in range(L):
+            got = WG[l].cpu().numpy()
+            # a weight gradient row is a sum over all vertices of signed terms: compare against the
+            # largest row of the matrix (rows that cancel to ~0 are ill-conditioned by themselves)
+            scale = np.abs(rWG[l]).max()
+            assert np.abs(got - rWG[l]).max() <= 1e-4 * max(scale, 1e-30), f"case {case} W_G[{l}]"
+
+
 def test_epoch_with_cached_input(mg, dev, ref):
     """MGGCN_MODEL_CACHE_INPUT: A^ X formed once, first layer without any SpMM in either pass;
     the same gradients as the oracle evaluating that layer in the (A^ X) W association."""
