@@ -79,6 +79,72 @@ __global__ __launch_bounds__(kThreads) void softmax_ce_kernel(int64_t n, int C, 
   }
 }
 
+// The same loss for rows of up to 64 * 8 classes, with the row held in registers: T lanes share a
+// row, each holding E elements (column tl + T*e), so logits are read once and written once and
+// one exponential is taken per element (softmax = exp(z - max) / sum, the label's entry again as
+// minus the sum of the others).  Same grid and same fixed-order loss partials as the general
+// kernel above.
+template <int E>
+__global__ __launch_bounds__(kThreads) void softmax_ce_rows(int64_t n, int C, int T, const float* Z, int64_t ldz,
+                                                             const int32_t* __restrict__ labels, float* dZ,
+                                                             int64_t ldd, float inv_n,
+                                                             float* __restrict__ block_loss) {
+  __shared__ float wave_loss[kThreads / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rows_per_wave = 64 / T;
+  const int tl = lane % T;
+  const int64_t wave_gid = (int64_t)blockIdx.x * (kThreads / 64) + wave;
+  const int64_t n_waves = (int64_t)gridDim.x * (kThreads / 64);
+  float loss_acc = 0.f;
+  for (int64_t base = wave_gid * rows_per_wave; base < n; base += n_waves * rows_per_wave) {
+    const int64_t row = base + lane / T;
+    const bool live = row < n;
+    const float* z = Z + (live ? row : 0) * ldz;
+    float v[E];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int c = tl + T * e;
+      v[e] = (live && c < C) ? z[c] : -INFINITY;
+      mx = fmaxf(mx, v[e]);
+    }
+    for (int d = 1; d < T; d <<= 1) mx = fmaxf(mx, __shfl_xor(mx, d));
+    const int y = live ? labels[row] : -1;
+    float s = 0.f, others = 0.f, zy = 0.f;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int c = tl + T * e;
+      const float ex = (live && c < C) ? expf(v[e] - mx) : 0.f;
+      s += ex;
+      if (c == y) zy = v[e]; else others += ex;
+      v[e] = ex;
+    }
+    for (int d = 1; d < T; d <<= 1) {
+      s += __shfl_xor(s, d);
+      others += __shfl_xor(others, d);
+      zy += __shfl_xor(zy, d);  // one lane of the team holds the label's logit, the rest 0
+    }
+    if (live) {
+      const float inv = 1.f / s;
+      if (tl == 0) loss_acc += mx + logf(s) - zy;
+      float* g = dZ + row * ldd;  // may be the same memory as z: the row is already in registers
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const int c = tl + T * e;
+        if (c < C) g[c] = (c == y ? -others : v[e]) * inv * inv_n;
+      }
+    }
+  }
+  for (int d = 1; d < 64; d <<= 1) loss_acc += __shfl_xor(loss_acc, d);
+  if (lane == 0) wave_loss[wave] = loss_acc;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+    for (int w = 0; w < kThreads / 64; ++w) t += wave_loss[w];
+    block_loss[blockIdx.x] = t;
+  }
+}
+
 __global__ __launch_bounds__(kThreads) void loss_finish(int64_t nblocks,
                                                          const float* __restrict__ block_loss,
                                                          double inv_n, float* __restrict__ loss) {
@@ -108,9 +174,11 @@ __global__ __launch_bounds__(kThreads) void adam_kernel(int64_t count, float* __
   W[i] -= lr * (mi * inv_c1) / (sqrtf(vi * inv_c2) + eps);
 }
 
+// Lanes per row: about four elements per lane (so that several narrow rows share a wavefront and a
+// lane still reads 16-lane-wide contiguous pieces), at least 4, at most 64.
 int team_lanes(int C) {
-  int t = 1;
-  while (t < C && t < 64) t <<= 1;
+  int t = 4;
+  while (t * 4 < C && t < 64) t <<= 1;
   return t;
 }
 
@@ -177,8 +245,18 @@ int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits, int64_t ld, cons
   MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "too many rows for one launch");
   hipStream_t s = as_stream(stream);
   float* block_loss = static_cast<float*>(ws);
-  softmax_ce_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n, C, team_lanes(C), logits, ld, labels, dlogits,
-                                                          ldd, (float)(1.0 / (double)n), block_loss);
+  const int T = team_lanes(C);
+  const float inv_n = (float)(1.0 / (double)n);
+  switch ((int)ceil_div(C, T)) {  // elements per lane
+    case 1: softmax_ce_rows<1><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 2: softmax_ce_rows<2><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 3: softmax_ce_rows<3><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 4: softmax_ce_rows<4><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 5: case 6: case 7: case 8:
+      softmax_ce_rows<8><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    default:  // more than 512 classes: the general kernel walks the row in passes
+      softmax_ce_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss);
+  }
   MGGCN_LAUNCH_CHECK();
   loss_finish<<<1, kThreads, 0, s>>>(blocks, block_loss, 1.0 / (double)n, loss_dev);
   MGGCN_LAUNCH_CHECK();

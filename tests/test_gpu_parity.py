@@ -434,7 +434,8 @@ def test_gemm_epilogues_beta_and_strides(mg, dev, ref):
 # a4 / a5: loss, ReLU'
 # ----------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("n,C,ld", [(4096, 8, 16), (1001, 41, 48), (333, 47, 47), (50, 100, 100), (7, 1, 4)])
+@pytest.mark.parametrize("n,C,ld", [(4096, 8, 16), (1001, 41, 48), (333, 47, 47), (50, 100, 100), (7, 1, 4),
+                                     (513, 256, 256), (300, 512, 512), (64, 513, 520), (100, 600, 600), (33, 17, 17)])
 def test_softmax_ce(mg, dev, ref, n, C, ld):
     say(f"[softmax_ce] n={n} C={C} ld={ld}")
     Zp = wl.normal_f32(n, 20, (n, ld)) * 3
