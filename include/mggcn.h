@@ -100,9 +100,24 @@ int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in
                         const int32_t* rowptr_out /*dev, from _count*/, int32_t* colidx_out /*dev*/,
                         float* val_out /*dev*/, void* ws, size_t ws_bytes, void* stream);
 
+/* The same two calls with 64-bit row offsets (input and output), for patterns whose entry count
+ * with the diagonal reaches 2^31 (up to 2^32 - 1; one row holds fewer than 2^31).  Same
+ * workspace size.  The 32-bit calls return MGGCN_E_OVERFLOW for such a pattern. */
+int mggcn_csr_normalize_count64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_in /*dev*/,
+                                const int32_t* colidx_in /*dev*/, int validate,
+                                int64_t* rowptr_out /*dev*/, int64_t* nnz_out /*host*/, void* ws,
+                                size_t ws_bytes, void* stream);
+
+int mggcn_csr_normalize64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_in /*dev*/,
+                          const int32_t* colidx_in /*dev*/, int mode /*mggcn_norm*/,
+                          const int32_t* deg_row /*dev or NULL*/, const int32_t* deg_col /*dev or NULL*/,
+                          const int64_t* rowptr_out /*dev, from _count64*/, int32_t* colidx_out /*dev*/,
+                          float* val_out /*dev*/, void* ws, size_t ws_bytes, void* stream);
+
 /* Explicit transpose of a CSR matrix (the paper keeps A^ and A^^T both, for the backward
  * SpMM of Eq. 9).  Rows of the result have ascending columns; the result is unique, so it
- * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries. */
+ * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries.  32-bit row offsets only
+ * (fewer than 2^31 entries). */
 size_t mggcn_csr_transpose_workspace_bytes(int32_t n_rows, int32_t n_cols, int64_t nnz);
 
 int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr,
@@ -134,6 +149,14 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr /*d
                        const int32_t* rowptr_t /*dev or NULL*/, const int32_t* colidx_t,
                        const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
                        mggcn_graph** out);
+/* The same with 64-bit row offsets, for matrices of 2^31 entries and more (fewer than 2^32: the
+ * segment tables hold entry offsets in 32 unsigned bits; a single row holds fewer than 2^29).
+ * Everything else about the handle is unchanged; the sweep form is not available for it. */
+int mggcn_graph_create64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr /*dev*/,
+                         const int32_t* colidx /*dev*/, const float* val /*dev*/,
+                         const int64_t* rowptr_t /*dev or NULL*/, const int32_t* colidx_t,
+                         const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
+                         mggcn_graph** out);
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max);
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws /*dev*/, size_t ws_bytes, void* stream);
 int mggcn_graph_destroy(mggcn_graph* g);

@@ -47,20 +47,24 @@ def mggcn_version() -> int:
 
 def mggcn_csr_normalize(n_rows, n_cols, rowptr_in, colidx_in, mode=NORM_SYM_SELFLOOP, deg_row=None,
                         deg_col=None, validate=False, stream=None):
-    """-> (rowptr, colidx, val) device tensors of the normalised adjacency with self-loops."""
+    """-> (rowptr, colidx, val) device tensors of the normalised adjacency with self-loops.
+    An int64 rowptr_in selects the 64-bit entry points (rowptr comes back as int64)."""
     torch = _torch()
     L = B.lib()
     dev = rowptr_in.device
     st = _stream(stream)
+    wide = rowptr_in.dtype == torch.int64
+    count_fn = L.mggcn_csr_normalize_count64 if wide else L.mggcn_csr_normalize_count
+    fill_fn = L.mggcn_csr_normalize64 if wide else L.mggcn_csr_normalize
     nbytes = L.mggcn_csr_normalize_workspace_bytes(n_rows, n_cols)
     ws = _ws(nbytes, dev)
-    rowptr = torch.empty(n_rows + 1, dtype=torch.int32, device=dev)
+    rowptr = torch.empty(n_rows + 1, dtype=rowptr_in.dtype, device=dev)
     nnz = C.c_int64(0)
-    B.check(L.mggcn_csr_normalize_count(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), int(validate),
+    B.check(count_fn(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), int(validate),
                                         B.ptr(rowptr), C.byref(nnz), _ws_ptr(ws), nbytes, st))
     colidx = torch.empty(nnz.value, dtype=torch.int32, device=dev)
     val = torch.empty(nnz.value, dtype=torch.float32, device=dev)
-    B.check(L.mggcn_csr_normalize(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), mode, B.ptr(deg_row),
+    B.check(fill_fn(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), mode, B.ptr(deg_row),
                                   B.ptr(deg_col), B.ptr(rowptr), B.ptr(colidx), B.ptr(val), _ws_ptr(ws),
                                   nbytes, st))
     torch.cuda.current_stream().synchronize() if stream is None else None  # ws may be freed now
@@ -97,7 +101,9 @@ class Graph:
         self._keep = [rowptr, colidx, val, transpose]
         rpt, cit, vat = transpose if transpose is not None else (None, None, None)
         h = C.c_void_p(None)
-        B.check(L.mggcn_graph_create(n_rows, n_cols, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rpt),
+        wide = str(rowptr.dtype).endswith("int64")  # 64-bit row offsets: matrices of 2^31 entries and more
+        create = L.mggcn_graph_create64 if wide else L.mggcn_graph_create
+        B.check(create(n_rows, n_cols, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rpt),
                                      B.ptr(cit), B.ptr(vat), seg_len, n_panels, _stream(stream), C.byref(h)))
         self.handle = h
         self.device = rowptr.device

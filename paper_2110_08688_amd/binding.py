@@ -29,9 +29,12 @@ SIGNATURES = {
     "mggcn_csr_normalize_workspace_bytes": (_sz, [_i32, _i32]),
     "mggcn_csr_normalize_count": (C.c_int, [_i32, _i32, _vp, _vp, C.c_int, _vp, C.POINTER(_i64), _vp, _sz, _vp]),
     "mggcn_csr_normalize": (C.c_int, [_i32, _i32, _vp, _vp, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "mggcn_csr_normalize_count64": (C.c_int, [_i32, _i32, _vp, _vp, C.c_int, _vp, C.POINTER(_i64), _vp, _sz, _vp]),
+    "mggcn_csr_normalize64": (C.c_int, [_i32, _i32, _vp, _vp, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mggcn_csr_transpose_workspace_bytes": (_sz, [_i32, _i32, _i64]),
     "mggcn_csr_transpose": (C.c_int, [_i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mggcn_graph_create": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(_vp)]),
+    "mggcn_graph_create64": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(_vp)]),
     "mggcn_graph_workspace_bytes": (_sz, [_vp, _i32]),
     "mggcn_graph_bind": (C.c_int, [_vp, _i32, _vp, _sz, _vp]),
     "mggcn_graph_destroy": (C.c_int, [_vp]),

@@ -62,5 +62,7 @@ inline hipStream_t as_stream(void* s) { return static_cast<hipStream_t>(s); }
 // inter-block waiting.
 size_t scan_tmp_ints(int64_t n);
 int exclusive_scan_i32(const int32_t* counts, int64_t n, int32_t* out, int32_t* tmp, hipStream_t s);
+// The same with 64-bit offsets (totals beyond 2^31); tmp needs scan_tmp_ints(n) int64 entries.
+int exclusive_scan_i64(const int32_t* counts, int64_t n, int64_t* out, int64_t* tmp, hipStream_t s);
 
 }  // namespace mggcn

@@ -13,7 +13,8 @@ namespace mggcn {
 //   first: no earlier launch has written this row, so the caller's beta applies (else beta = 1)
 //   last : no later launch adds to this row, so the epilogue is applied here
 struct Task {
-  int32_t row, k0;
+  int32_t row;
+  uint32_t k0;  // entry offsets are held in 32 unsigned bits: fewer than 2^32 entries per matrix
   uint32_t len_flags;
   int32_t slot;  // < 0: result goes to Y; else index into the partial-sum table
 };
@@ -72,7 +73,8 @@ constexpr int64_t kSweepTeamPad = 256;
 struct Orientation {
   int32_t n_rows = 0, n_cols = 0;
   int64_t nnz = 0;
-  const int32_t* rowptr = nullptr;
+  const void* rowptr = nullptr;  // device array of n_rows + 1 offsets, int32_t or (wide) int64_t
+  bool wide = false;
   const int32_t* colidx = nullptr;
   const float* val = nullptr;
   TaskSet flat;      // one panel

@@ -22,13 +22,17 @@ __device__ inline int lower_bound_dev(const int32_t* __restrict__ a, int n, int 
   return lo;
 }
 
+// IT: type of the row offsets, int32_t or int64_t (entry counts beyond 2^31); a single row is
+// always shorter than 2^31.
+template <typename IT>
 __global__ __launch_bounds__(kThreads) void count_rows(int32_t n_rows, int32_t n_cols,
-                                                        const int32_t* __restrict__ rowptr,
+                                                        const IT* __restrict__ rowptr,
                                                         const int32_t* __restrict__ colidx,
                                                         int32_t* __restrict__ counts) {
   const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
   if (i >= n_rows) return;
-  const int32_t b = rowptr[i], deg = rowptr[i + 1] - b;
+  const IT b = rowptr[i];
+  const int32_t deg = (int32_t)(rowptr[i + 1] - b);
   int add = 0;
   if (i < n_cols) {
     const int p = lower_bound_dev(colidx + b, deg, (int)i);
@@ -39,19 +43,20 @@ __global__ __launch_bounds__(kThreads) void count_rows(int32_t n_rows, int32_t n
 
 // flag bit 0: rowptr not monotone / negative; bit 1: column out of range; bit 2: row not
 // strictly ascending
+template <typename IT>
 __global__ __launch_bounds__(kThreads) void validate_rows(int32_t n_rows, int32_t n_cols,
-                                                           const int32_t* __restrict__ rowptr,
+                                                           const IT* __restrict__ rowptr,
                                                            const int32_t* __restrict__ colidx,
-                                                           int32_t nnz, int32_t* flag) {
+                                                           int64_t nnz, int32_t* flag) {
   const int lane = threadIdx.x & 63;
   const int64_t row = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
   if (row >= n_rows) return;
-  const int32_t b = rowptr[row], e = rowptr[row + 1];
+  const int64_t b = rowptr[row], e = rowptr[row + 1];
   int bad = 0;
-  if (b < 0 || e < b || e > nnz) {
+  if (b < 0 || e < b || e > nnz || e - b > INT32_MAX) {
     bad = 1;
   } else {
-    for (int32_t k = b + lane; k < e; k += 64) {
+    for (int64_t k = b + lane; k < e; k += 64) {
       const int32_t j = colidx[k];
       if (j < 0 || j >= n_cols) bad |= 2;
       if (k > b && colidx[k - 1] >= j) bad |= 4;
@@ -61,20 +66,20 @@ __global__ __launch_bounds__(kThreads) void validate_rows(int32_t n_rows, int32_
 }
 
 // One wavefront per row.
-template <bool kValues>
+template <bool kValues, typename IT>
 __global__ __launch_bounds__(kThreads) void fill_rows(int32_t n_rows, int32_t n_cols,
-                                                       const int32_t* __restrict__ rowptr_in,
+                                                       const IT* __restrict__ rowptr_in,
                                                        const int32_t* __restrict__ colidx_in,
                                                        const int32_t* __restrict__ deg_row,
                                                        const int32_t* __restrict__ deg_col,
-                                                       const int32_t* __restrict__ rowptr_out,
+                                                       const IT* __restrict__ rowptr_out,
                                                        int32_t* __restrict__ colidx_out,
                                                        float* __restrict__ val_out) {
   const int lane = threadIdx.x & 63;
   const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
   if (i >= n_rows) return;
-  const int32_t b = rowptr_in[i], deg = rowptr_in[i + 1] - b;
-  const int32_t ob = rowptr_out[i], odeg = rowptr_out[i + 1] - ob;
+  const IT b = rowptr_in[i], ob = rowptr_out[i];
+  const int32_t deg = (int32_t)(rowptr_in[i + 1] - b), odeg = (int32_t)(rowptr_out[i + 1] - ob);
   const bool insert = odeg != deg;  // the diagonal is missing from the input row
   const int p = insert ? lower_bound_dev(colidx_in + b, deg, (int)i) : 0;
   double di = 0.0;
@@ -122,7 +127,7 @@ size_t carve(int32_t n_rows, int32_t n_cols, void* ws, NormWs* out) {
   Carver c(ws);
   NormWs w;
   w.counts = c.take<int32_t>((size_t)n_rows + 1);
-  w.scan_tmp = c.take<int32_t>(scan_tmp_ints(n_rows));
+  w.scan_tmp = c.take<int32_t>(2 * scan_tmp_ints(n_rows));  // room for 64-bit offsets
   w.colcount = c.take<int32_t>((size_t)n_cols + 1);
   w.flag = c.take<int32_t>(64);
   if (out) *out = w;
@@ -143,21 +148,10 @@ int check_common(int32_t n_rows, int32_t n_cols, const void* rowptr_in, const vo
   return MGGCN_OK;
 }
 
-}  // namespace
-}  // namespace mggcn
-
-using namespace mggcn;
-
-extern "C" {
-
-size_t mggcn_csr_normalize_workspace_bytes(int32_t n_rows, int32_t n_cols) {
-  if (n_rows < 0 || n_cols < 0) return 0;
-  return carve(n_rows, n_cols, nullptr, nullptr);
-}
-
-int mggcn_csr_normalize_count(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in,
-                              const int32_t* colidx_in, int validate, int32_t* rowptr_out,
-                              int64_t* nnz_out, void* ws, size_t ws_bytes, void* stream) {
+template <typename IT>
+int normalize_count_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr_in, const int32_t* colidx_in,
+                         int validate, IT* rowptr_out, int64_t* nnz_out, void* ws, size_t ws_bytes,
+                         void* stream) {
   int rc = check_common(n_rows, n_cols, rowptr_in, colidx_in, ws, ws_bytes);
   if (rc) return rc;
   MGGCN_REQUIRE(rowptr_out && nnz_out, MGGCN_E_INVALID_ARG, "rowptr_out / nnz_out is NULL");
@@ -165,22 +159,27 @@ int mggcn_csr_normalize_count(int32_t n_rows, int32_t n_cols, const int32_t* row
   NormWs w;
   carve(n_rows, n_cols, ws, &w);
 
-  int32_t nnz_in = 0;
-  MGGCN_HIP(hipMemcpyAsync(&nnz_in, rowptr_in + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  IT nnz_in = 0;
+  MGGCN_HIP(hipMemcpyAsync(&nnz_in, rowptr_in + n_rows, sizeof(IT), hipMemcpyDeviceToHost, s));
   MGGCN_HIP(hipStreamSynchronize(s));
-  MGGCN_REQUIRE(nnz_in >= 0, MGGCN_E_BAD_CSR, "rowptr_in[n_rows] = %d is negative", nnz_in);
+  MGGCN_REQUIRE(nnz_in >= 0, MGGCN_E_BAD_CSR, "rowptr_in[n_rows] = %lld is negative", (long long)nnz_in);
   MGGCN_REQUIRE(nnz_in == 0 || colidx_in != nullptr, MGGCN_E_INVALID_ARG, "colidx_in is NULL");
   const int64_t worst = (int64_t)nnz_in + (n_rows < n_cols ? n_rows : n_cols);
-  MGGCN_REQUIRE(worst < INT32_MAX, MGGCN_E_OVERFLOW,
-                "pattern with self-loops may reach %lld entries, int32 indexing holds 2^31-1",
-                (long long)worst);
+  if (sizeof(IT) == 4)
+    MGGCN_REQUIRE(worst < INT32_MAX, MGGCN_E_OVERFLOW,
+                  "pattern with self-loops may reach %lld entries, int32 offsets hold 2^31-1: use the 64-bit form",
+                  (long long)worst);
+  else
+    MGGCN_REQUIRE(worst < ((int64_t)1 << 32), MGGCN_E_OVERFLOW,
+                  "pattern with self-loops may reach %lld entries, the library holds fewer than 2^32",
+                  (long long)worst);
 
   if (validate) {
     zero_i32<<<1, 64, 0, s>>>(w.flag, 1);
     MGGCN_LAUNCH_CHECK();
     if (n_rows > 0) {
-      validate_rows<<<(unsigned)ceil_div((int64_t)n_rows * 64, kThreads), kThreads, 0, s>>>(
-          n_rows, n_cols, rowptr_in, colidx_in, nnz_in, w.flag);
+      validate_rows<IT><<<(unsigned)ceil_div((int64_t)n_rows * 64, kThreads), kThreads, 0, s>>>(
+          n_rows, n_cols, rowptr_in, colidx_in, (int64_t)nnz_in, w.flag);
       MGGCN_LAUNCH_CHECK();
     }
     int32_t flag = 0;
@@ -193,23 +192,26 @@ int mggcn_csr_normalize_count(int32_t n_rows, int32_t n_cols, const int32_t* row
   }
 
   if (n_rows > 0) {
-    count_rows<<<(unsigned)ceil_div(n_rows, kThreads), kThreads, 0, s>>>(n_rows, n_cols, rowptr_in,
-                                                                         colidx_in, w.counts);
+    count_rows<IT><<<(unsigned)ceil_div(n_rows, kThreads), kThreads, 0, s>>>(n_rows, n_cols, rowptr_in,
+                                                                             colidx_in, w.counts);
     MGGCN_LAUNCH_CHECK();
   }
-  rc = exclusive_scan_i32(w.counts, n_rows, rowptr_out, w.scan_tmp, s);
+  if constexpr (sizeof(IT) == 4)
+    rc = exclusive_scan_i32(w.counts, n_rows, rowptr_out, w.scan_tmp, s);
+  else
+    rc = exclusive_scan_i64(w.counts, n_rows, rowptr_out, reinterpret_cast<int64_t*>(w.scan_tmp), s);
   if (rc) return rc;
-  int32_t total = 0;
-  MGGCN_HIP(hipMemcpyAsync(&total, rowptr_out + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  IT total = 0;
+  MGGCN_HIP(hipMemcpyAsync(&total, rowptr_out + n_rows, sizeof(IT), hipMemcpyDeviceToHost, s));
   MGGCN_HIP(hipStreamSynchronize(s));
   *nnz_out = total;
   return MGGCN_OK;
 }
 
-int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in,
-                        const int32_t* colidx_in, int mode, const int32_t* deg_row,
-                        const int32_t* deg_col, const int32_t* rowptr_out, int32_t* colidx_out,
-                        float* val_out, void* ws, size_t ws_bytes, void* stream) {
+template <typename IT>
+int normalize_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr_in, const int32_t* colidx_in, int mode,
+                   const int32_t* deg_row, const int32_t* deg_col, const IT* rowptr_out, int32_t* colidx_out,
+                   float* val_out, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_common(n_rows, n_cols, rowptr_in, colidx_in, ws, ws_bytes);
   if (rc) return rc;
   MGGCN_REQUIRE(mode == MGGCN_NORM_SYM_SELFLOOP || mode == MGGCN_NORM_MEAN_IN, MGGCN_E_INVALID_ARG,
@@ -226,16 +228,16 @@ int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in
   carve(n_rows, n_cols, ws, &w);
   const unsigned row_blocks = (unsigned)ceil_div((int64_t)n_rows * 64, kThreads);
   if (mode == MGGCN_NORM_SYM_SELFLOOP) {
-    fill_rows<true><<<row_blocks, kThreads, 0, s>>>(n_rows, n_cols, rowptr_in, colidx_in, deg_row,
+    fill_rows<true, IT><<<row_blocks, kThreads, 0, s>>>(n_rows, n_cols, rowptr_in, colidx_in, deg_row,
                                                     deg_col, rowptr_out, colidx_out, val_out);
     MGGCN_LAUNCH_CHECK();
     return MGGCN_OK;
   }
-  fill_rows<false><<<row_blocks, kThreads, 0, s>>>(n_rows, n_cols, rowptr_in, colidx_in, nullptr,
+  fill_rows<false, IT><<<row_blocks, kThreads, 0, s>>>(n_rows, n_cols, rowptr_in, colidx_in, nullptr,
                                                    nullptr, rowptr_out, colidx_out, val_out);
   MGGCN_LAUNCH_CHECK();
-  int32_t nnz = 0;
-  MGGCN_HIP(hipMemcpyAsync(&nnz, rowptr_out + n_rows, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  IT nnz = 0;
+  MGGCN_HIP(hipMemcpyAsync(&nnz, rowptr_out + n_rows, sizeof(IT), hipMemcpyDeviceToHost, s));
   MGGCN_HIP(hipStreamSynchronize(s));
   const int32_t* cc = deg_col;
   if (!cc) {
@@ -243,16 +245,58 @@ int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in
                                                                                    (int64_t)n_cols + 1);
     MGGCN_LAUNCH_CHECK();
     if (nnz > 0) {
-      column_histogram<<<(unsigned)ceil_div(nnz, kThreads), kThreads, 0, s>>>(nnz, colidx_out, w.colcount);
+      column_histogram<<<(unsigned)ceil_div((int64_t)nnz, kThreads), kThreads, 0, s>>>((int64_t)nnz, colidx_out, w.colcount);
       MGGCN_LAUNCH_CHECK();
     }
     cc = w.colcount;
   }
   if (nnz > 0) {
-    mean_values<<<(unsigned)ceil_div(nnz, kThreads), kThreads, 0, s>>>(nnz, colidx_out, cc, val_out);
+    mean_values<<<(unsigned)ceil_div((int64_t)nnz, kThreads), kThreads, 0, s>>>((int64_t)nnz, colidx_out, cc, val_out);
     MGGCN_LAUNCH_CHECK();
   }
   return MGGCN_OK;
+}
+
+}  // namespace
+}  // namespace mggcn
+
+using namespace mggcn;
+
+extern "C" {
+
+size_t mggcn_csr_normalize_workspace_bytes(int32_t n_rows, int32_t n_cols) {
+  if (n_rows < 0 || n_cols < 0) return 0;
+  return carve(n_rows, n_cols, nullptr, nullptr);
+}
+
+int mggcn_csr_normalize_count(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in,
+                              const int32_t* colidx_in, int validate, int32_t* rowptr_out,
+                              int64_t* nnz_out, void* ws, size_t ws_bytes, void* stream) {
+  return normalize_count_impl<int32_t>(n_rows, n_cols, rowptr_in, colidx_in, validate, rowptr_out, nnz_out, ws,
+                                       ws_bytes, stream);
+}
+
+int mggcn_csr_normalize_count64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_in,
+                                const int32_t* colidx_in, int validate, int64_t* rowptr_out,
+                                int64_t* nnz_out, void* ws, size_t ws_bytes, void* stream) {
+  return normalize_count_impl<int64_t>(n_rows, n_cols, rowptr_in, colidx_in, validate, rowptr_out, nnz_out, ws,
+                                       ws_bytes, stream);
+}
+
+int mggcn_csr_normalize(int32_t n_rows, int32_t n_cols, const int32_t* rowptr_in,
+                        const int32_t* colidx_in, int mode, const int32_t* deg_row,
+                        const int32_t* deg_col, const int32_t* rowptr_out, int32_t* colidx_out,
+                        float* val_out, void* ws, size_t ws_bytes, void* stream) {
+  return normalize_impl<int32_t>(n_rows, n_cols, rowptr_in, colidx_in, mode, deg_row, deg_col, rowptr_out,
+                                 colidx_out, val_out, ws, ws_bytes, stream);
+}
+
+int mggcn_csr_normalize64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_in,
+                          const int32_t* colidx_in, int mode, const int32_t* deg_row,
+                          const int32_t* deg_col, const int64_t* rowptr_out, int32_t* colidx_out,
+                          float* val_out, void* ws, size_t ws_bytes, void* stream) {
+  return normalize_impl<int64_t>(n_rows, n_cols, rowptr_in, colidx_in, mode, deg_row, deg_col, rowptr_out,
+                                 colidx_out, val_out, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

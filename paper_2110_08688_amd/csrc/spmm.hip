@@ -43,7 +43,7 @@ constexpr int kDefaultSegLen = 2048;
 
 // Row-segment tables for `n_panels` column panels.  colidx (host copy) is only needed when
 // n_panels > 1.
-void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vector<int32_t>& rowptr,
+void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vector<int64_t>& rowptr,
                     const int32_t* colidx, int32_t n_panels, int32_t seg_len) {
   const int32_t P = std::max(n_panels, 1);
   const int64_t width = ceil_div(std::max(n_cols, 1), P);
@@ -51,31 +51,32 @@ void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vect
   std::vector<std::vector<Task>> per_panel((size_t)P);
   std::vector<std::vector<FixRow>> per_panel_fix((size_t)P);
   std::vector<int64_t> slots((size_t)P, 0);
-  std::vector<int32_t> cut((size_t)P + 1);
+  std::vector<int64_t> cut((size_t)P + 1);
   for (int32_t i = 0; i < n_rows; ++i) {
-    const int32_t b = rowptr[i], e = rowptr[(size_t)i + 1];
+    const int64_t b = rowptr[i], e = rowptr[(size_t)i + 1];
     cut[0] = b;
     cut[(size_t)P] = e;
     for (int32_t p = 1; p < P; ++p)
-      cut[p] = (int32_t)(std::lower_bound(colidx + cut[p - 1], colidx + e, (int32_t)std::min<int64_t>(p * width, n_cols)) - colidx);
+      cut[p] = (int64_t)(std::lower_bound(colidx + cut[p - 1], colidx + e, (int32_t)std::min<int64_t>(p * width, n_cols)) - colidx);
     int32_t first = -1, last = -1;
     for (int32_t p = 0; p < P; ++p)
       if (cut[(size_t)p + 1] > cut[p]) { if (first < 0) first = p; last = p; }
     if (first < 0) first = last = 0;  // empty row: one empty task that still writes beta*Y / zeros
     for (int32_t p = first; p <= last; ++p) {
-      const int32_t lo = cut[p], len = cut[(size_t)p + 1] - lo;
+      const int64_t lo = cut[p];
+      const int32_t len = (int32_t)(cut[(size_t)p + 1] - lo);  // a row is shorter than 2^29 (checked by the caller)
       if (len == 0 && !(p == first && first == last)) continue;
       const uint32_t flags = (p == first ? kTaskFirst : 0u) | (p == last ? kTaskLast : 0u);
       if (len <= seg_len) {
-        per_panel[p].push_back({i, lo, (uint32_t)len | flags, -1});
+        per_panel[p].push_back({i, (uint32_t)lo, (uint32_t)len | flags, -1});
       } else {
         const int32_t nseg = (int32_t)ceil_div(len, seg_len);
         const int32_t piece = (int32_t)ceil_div(len, nseg);
         per_panel_fix[p].push_back({i, (int32_t)slots[p], nseg, flags});
         for (int32_t s = 0; s < nseg; ++s) {
-          const int32_t k0 = lo + s * piece;
-          const int32_t k1 = std::min(lo + len, k0 + piece);
-          per_panel[p].push_back({i, k0, (uint32_t)(k1 - k0), (int32_t)slots[p]++});
+          const int64_t k0 = lo + (int64_t)s * piece;
+          const int64_t k1 = std::min<int64_t>(lo + len, k0 + piece);
+          per_panel[p].push_back({i, (uint32_t)k0, (uint32_t)(k1 - k0), (int32_t)slots[p]++});
         }
       }
     }
@@ -257,6 +258,7 @@ int32_t default_sweep_rows() {
 }
 
 int build_sweep_for(Orientation* o, int32_t n_panels, int32_t rows_per_team, hipStream_t s) {
+  MGGCN_REQUIRE(!o->wide, MGGCN_E_UNSUPPORTED, "the sweep form is built from 32-bit row offsets only");
   std::vector<int32_t> rp((size_t)o->n_rows + 1), ci((size_t)o->nnz);
   std::vector<float> va((size_t)o->nnz);
   MGGCN_HIP(hipMemcpyAsync(rp.data(), o->rowptr, sizeof(int32_t) * rp.size(), hipMemcpyDeviceToHost, s));
@@ -273,6 +275,101 @@ int build_sweep_for(Orientation* o, int32_t n_panels, int32_t rows_per_team, hip
 }  // namespace mggcn
 
 namespace mggcn {
+namespace {
+
+template <typename IT>
+int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const int32_t* colidx, const float* val,
+                      const IT* rowptr_t, const int32_t* colidx_t, const float* val_t, int32_t seg_len,
+                      int32_t n_panels, void* stream, mggcn_graph** out) {
+  MGGCN_REQUIRE(out != nullptr, MGGCN_E_INVALID_ARG, "out is NULL");
+  *out = nullptr;
+  MGGCN_REQUIRE(n_rows >= 0 && n_cols >= 0, MGGCN_E_INVALID_ARG, "negative matrix size %d x %d",
+                n_rows, n_cols);
+  MGGCN_REQUIRE(rowptr != nullptr, MGGCN_E_INVALID_ARG, "rowptr is NULL");
+  MGGCN_REQUIRE(seg_len >= 0 && seg_len <= (1 << 20), MGGCN_E_INVALID_ARG,
+                "seg_len %d outside [0, 2^20]", seg_len);
+  MGGCN_REQUIRE(rowptr_t != nullptr || n_rows == n_cols, MGGCN_E_INVALID_ARG,
+                "a %d x %d matrix cannot be declared symmetric: pass its transpose", n_rows, n_cols);
+  MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 64, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 64]",
+                n_panels);
+  if (seg_len == 0) {
+    seg_len = kDefaultSegLen;
+    if (const char* e = std::getenv("MGGCN_SEG_LEN")) {
+      const int v = std::atoi(e);
+      if (v >= 8 && v <= (1 << 20)) seg_len = v;
+    }
+  }
+  seg_len = std::max(seg_len, 8);
+  hipStream_t s = as_stream(stream);
+
+  mggcn_graph* g = new (std::nothrow) mggcn_graph;
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
+  g->symmetric = (rowptr_t == nullptr);
+  g->seg_len = seg_len;
+  g->panel_bytes = 16ll << 20;
+  g->panels_fixed = n_panels > 1;
+  if (const char* e = std::getenv("MGGCN_CHUNK_LANES")) {
+    const int v = std::atoi(e);
+    if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) g->chunk_lanes = v;
+  }
+  if (const char* e = std::getenv("MGGCN_PANEL_MB")) {
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= (1 << 20)) g->panel_bytes = (int64_t)v << 20;
+  }
+  if (n_panels == 0)
+    if (const char* e = std::getenv("MGGCN_PANELS")) {
+      const int v = std::atoi(e);
+      if (v >= 1 && v <= 64) { n_panels = v; g->panels_fixed = v > 1; }
+    }
+
+  auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const IT* rp, const int32_t* ci,
+                   const float* va) -> int {
+    o->n_rows = nr; o->n_cols = nc; o->rowptr = rp; o->wide = sizeof(IT) == 8; o->colidx = ci; o->val = va;
+    std::vector<IT> raw((size_t)nr + 1);
+    MGGCN_HIP(hipMemcpyAsync(raw.data(), rp, sizeof(IT) * ((size_t)nr + 1), hipMemcpyDeviceToHost, s));
+    MGGCN_HIP(hipStreamSynchronize(s));
+    std::vector<int64_t> h(raw.begin(), raw.end());
+    std::vector<IT>().swap(raw);
+    MGGCN_REQUIRE(h[0] == 0, MGGCN_E_BAD_CSR, "rowptr[0] = %lld, expected 0", (long long)h[0]);
+    for (int32_t i = 0; i < nr; ++i) {
+      MGGCN_REQUIRE(h[(size_t)i + 1] >= h[i], MGGCN_E_BAD_CSR, "rowptr decreases at row %d", i);
+      MGGCN_REQUIRE(h[(size_t)i + 1] - h[i] <= (int64_t)kTaskLenMask, MGGCN_E_OVERFLOW,
+                    "row %d holds %lld entries, a row may hold 2^29 - 1", i, (long long)(h[(size_t)i + 1] - h[i]));
+    }
+    o->nnz = h[nr];
+    MGGCN_REQUIRE(o->nnz < ((int64_t)1 << 32), MGGCN_E_OVERFLOW,
+                  "%lld entries: entry offsets are held in 32 unsigned bits", (long long)o->nnz);
+    MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
+    build_task_set(&o->flat, nr, nc, h, nullptr, 1, seg_len);
+    const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
+    if (Pmax > 1) {
+      // panel cuts need the column indices: one read-back, setup only
+      std::vector<int32_t> hc((size_t)o->nnz);
+      MGGCN_HIP(hipMemcpyAsync(hc.data(), ci, sizeof(int32_t) * (size_t)o->nnz, hipMemcpyDeviceToHost, s));
+      MGGCN_HIP(hipStreamSynchronize(s));
+      for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
+        o->panelled.emplace_back();
+        build_task_set(&o->panelled.back(), nr, nc, h, hc.data(), P, seg_len);
+      }
+    }
+    // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
+    // and lose the shared panel), so it is built only on request.
+    if (n_panels == 0 && sweep_pays(nr, nc, o->nnz) && std::getenv("MGGCN_SWEEP"))
+      return build_sweep_for(o, default_sweep_panels(nc), default_sweep_rows(), s);
+    return MGGCN_OK;
+  };
+  int rc = setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val);
+  if (!rc && !g->symmetric) rc = setup(&g->bwd, n_cols, n_rows, rowptr_t, colidx_t, val_t);
+  if (!rc && !g->symmetric)
+    if (g->bwd.nnz != g->fwd.nnz)
+      rc = fail(MGGCN_E_BAD_CSR, "transpose has %lld entries, matrix has %lld",
+                (long long)g->bwd.nnz, (long long)g->fwd.nnz);
+  if (rc) { delete g; return rc; }
+  *out = g;
+  return MGGCN_OK;
+}
+
+}  // namespace
 
 int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int32_t F, float beta,
                     int epilogue, const float* Y, int64_t ldy) {
@@ -385,85 +482,16 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr, co
                        const float* val, const int32_t* rowptr_t, const int32_t* colidx_t,
                        const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
                        mggcn_graph** out) {
-  MGGCN_REQUIRE(out != nullptr, MGGCN_E_INVALID_ARG, "out is NULL");
-  *out = nullptr;
-  MGGCN_REQUIRE(n_rows >= 0 && n_cols >= 0, MGGCN_E_INVALID_ARG, "negative matrix size %d x %d",
-                n_rows, n_cols);
-  MGGCN_REQUIRE(rowptr != nullptr, MGGCN_E_INVALID_ARG, "rowptr is NULL");
-  MGGCN_REQUIRE(seg_len >= 0 && seg_len <= (1 << 20), MGGCN_E_INVALID_ARG,
-                "seg_len %d outside [0, 2^20]", seg_len);
-  MGGCN_REQUIRE(rowptr_t != nullptr || n_rows == n_cols, MGGCN_E_INVALID_ARG,
-                "a %d x %d matrix cannot be declared symmetric: pass its transpose", n_rows, n_cols);
-  MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 64, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 64]",
-                n_panels);
-  if (seg_len == 0) {
-    seg_len = kDefaultSegLen;
-    if (const char* e = std::getenv("MGGCN_SEG_LEN")) {
-      const int v = std::atoi(e);
-      if (v >= 8 && v <= (1 << 20)) seg_len = v;
-    }
-  }
-  seg_len = std::max(seg_len, 8);
-  hipStream_t s = as_stream(stream);
+  return graph_create_impl<int32_t>(n_rows, n_cols, rowptr, colidx, val, rowptr_t, colidx_t, val_t, seg_len,
+                                    n_panels, stream, out);
+}
 
-  mggcn_graph* g = new (std::nothrow) mggcn_graph;
-  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
-  g->symmetric = (rowptr_t == nullptr);
-  g->seg_len = seg_len;
-  g->panel_bytes = 16ll << 20;
-  g->panels_fixed = n_panels > 1;
-  if (const char* e = std::getenv("MGGCN_CHUNK_LANES")) {
-    const int v = std::atoi(e);
-    if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) g->chunk_lanes = v;
-  }
-  if (const char* e = std::getenv("MGGCN_PANEL_MB")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= (1 << 20)) g->panel_bytes = (int64_t)v << 20;
-  }
-  if (n_panels == 0)
-    if (const char* e = std::getenv("MGGCN_PANELS")) {
-      const int v = std::atoi(e);
-      if (v >= 1 && v <= 64) { n_panels = v; g->panels_fixed = v > 1; }
-    }
-
-  auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const int32_t* rp, const int32_t* ci,
-                   const float* va) -> int {
-    o->n_rows = nr; o->n_cols = nc; o->rowptr = rp; o->colidx = ci; o->val = va;
-    std::vector<int32_t> h((size_t)nr + 1);
-    MGGCN_HIP(hipMemcpyAsync(h.data(), rp, sizeof(int32_t) * ((size_t)nr + 1), hipMemcpyDeviceToHost, s));
-    MGGCN_HIP(hipStreamSynchronize(s));
-    MGGCN_REQUIRE(h[0] == 0, MGGCN_E_BAD_CSR, "rowptr[0] = %d, expected 0", h[0]);
-    for (int32_t i = 0; i < nr; ++i)
-      MGGCN_REQUIRE(h[(size_t)i + 1] >= h[i], MGGCN_E_BAD_CSR, "rowptr decreases at row %d", i);
-    o->nnz = h[nr];
-    MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
-    build_task_set(&o->flat, nr, nc, h, nullptr, 1, seg_len);
-    const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
-    if (Pmax > 1) {
-      // panel cuts need the column indices: one read-back, setup only
-      std::vector<int32_t> hc((size_t)o->nnz);
-      MGGCN_HIP(hipMemcpyAsync(hc.data(), ci, sizeof(int32_t) * (size_t)o->nnz, hipMemcpyDeviceToHost, s));
-      MGGCN_HIP(hipStreamSynchronize(s));
-      for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
-        o->panelled.emplace_back();
-        build_task_set(&o->panelled.back(), nr, nc, h, hc.data(), P, seg_len);
-      }
-    }
-    // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
-    // and lose the shared panel), so it is built only on request.
-    if (n_panels == 0 && sweep_pays(nr, nc, o->nnz) && std::getenv("MGGCN_SWEEP"))
-      return build_sweep_for(o, default_sweep_panels(nc), default_sweep_rows(), s);
-    return MGGCN_OK;
-  };
-  int rc = setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val);
-  if (!rc && !g->symmetric) rc = setup(&g->bwd, n_cols, n_rows, rowptr_t, colidx_t, val_t);
-  if (!rc && !g->symmetric)
-    if (g->bwd.nnz != g->fwd.nnz)
-      rc = fail(MGGCN_E_BAD_CSR, "transpose has %lld entries, matrix has %lld",
-                (long long)g->bwd.nnz, (long long)g->fwd.nnz);
-  if (rc) { delete g; return rc; }
-  *out = g;
-  return MGGCN_OK;
+int mggcn_graph_create64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr, const int32_t* colidx,
+                         const float* val, const int64_t* rowptr_t, const int32_t* colidx_t,
+                         const float* val_t, int32_t seg_len, int32_t n_panels, void* stream,
+                         mggcn_graph** out) {
+  return graph_create_impl<int64_t>(n_rows, n_cols, rowptr, colidx, val, rowptr_t, colidx_t, val_t, seg_len,
+                                    n_panels, stream, out);
 }
 
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max) {

@@ -81,7 +81,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
   const int team_base = team * TEAM;
   const int64_t t = (tb * (kSpmmThreads / 64) + wave) * TPW + team;
 
-  Task task = {0, 0, 0u, -1};
+  Task task = {0, 0u, 0u, -1};
   const bool has_task = t < ntasks;
   if (has_task) task = tasks[t];
   const int len = (int)(task.len_flags & kTaskLenMask);
@@ -101,8 +101,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
   const int nf = min(VW, max(0, F - f0));
   const bool live = nf > 0;  // this lane covers at least one feature column
   const char* __restrict__ xbase = reinterpret_cast<const char*>(X + f0);
-  const int32_t* __restrict__ cptr = colidx + task.k0 + tl;
-  const float* __restrict__ vptr = val + task.k0 + tl;
+  const int32_t* __restrict__ cptr = colidx + ((size_t)task.k0 + tl);
+  const float* __restrict__ vptr = val + ((size_t)task.k0 + tl);
 
   using Op = Operand<XT, VW>;
   float acc[VW];

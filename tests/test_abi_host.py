@@ -80,6 +80,19 @@ def test_argument_errors_need_no_device(B):
     assert L.mggcn_graph_create(3, 3, None, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
     assert L.mggcn_graph_create(3, 3, 256, 256, 256, None, None, None, 0, 65, None, C.byref(h)) == B.E_INVALID_ARG
     assert L.mggcn_spmm(None, 0, 256, 4, 4, 0.0, 0, 256, 4, None) == B.E_INVALID_ARG
+    # the 64-bit-offset forms and the bfloat16 forms check their arguments the same way
+    assert L.mggcn_graph_create64(-3, 3, 256, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create64(3, 4, 256, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_graph_create64(3, 3, None, 256, 256, None, None, None, 0, 0, None, C.byref(h)) == B.E_INVALID_ARG
+    assert L.mggcn_csr_normalize_count64(4, 4, None, 256, 0, 256, C.byref(nnz), 256, 1 << 20, None) == B.E_INVALID_ARG
+    assert L.mggcn_csr_normalize_count64(4, 4, 256, 256, 0, 256, C.byref(nnz), 256, 8, None) == B.E_WORKSPACE
+    assert L.mggcn_csr_normalize64(4, 9, 256, 256, 0, None, None, 256, 256, 256, 256, 1 << 20, None) == B.E_INVALID_ARG
+    assert L.mggcn_spmm_bf16(None, 0, 256, 8, 8, 0.0, 0, 256, 8, None) == B.E_INVALID_ARG
+    assert L.mggcn_f32_to_bf16(-1, 4, 256, 4, 256, 4, None) == B.E_INVALID_ARG
+    assert L.mggcn_f32_to_bf16(4, 4, 256, 3, 256, 4, None) == B.E_INVALID_ARG
+    assert L.mggcn_f32_to_bf16(4, 4, None, 4, 256, 4, None) == B.E_INVALID_ARG
+    assert L.mggcn_f32_to_bf16(0, 4, None, 4, None, 4, None) == B.OK
+    assert L.mggcn_model_gather_operand(None, 4, None, None) == B.E_INVALID_ARG
     # loss / relu
     assert L.mggcn_softmax_ce(0, 4, 256, 4, 256, 256, 256, 4, 256, 1024, None) == B.E_INVALID_ARG
     assert L.mggcn_softmax_ce(8, 4, 256, 3, 256, 256, 256, 4, 256, 1024, None) == B.E_INVALID_ARG
