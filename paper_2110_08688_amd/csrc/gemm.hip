@@ -12,7 +12,7 @@
 //
 // The shapes here are tall and skinny (M = vertex count, N and K a few hundred at most) except
 // for the weight gradient, whose inner dimension is the vertex count: that one is split along
-// K over blockIdx.z into partial products that a second kernel adds in split order (no
+// K into partial products that a second kernel adds in split order (no
 // floating-point atomics, so results are reproducible).
 #include "common.h"
 
@@ -22,6 +22,7 @@ namespace mggcn {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
 typedef float float16v __attribute__((ext_vector_type(16)));
 
@@ -175,9 +176,30 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  const int64_t m0 = m_base + (int64_t)blockIdx.x * BM;
-  const int64_t n0 = (int64_t)blockIdx.y * BN;
-  const int64_t kb = (int64_t)blockIdx.z * k_per_split;
+  // Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.  The
+  // 1-D grid is therefore decoded so that the N tiles of one M tile -- they re-read the same rows
+  // of A -- sit on one XCD next to each other in time.  Measured on 2.45M x 256 x 256: 3.33 ->
+  // 2.91 ms, A being fetched from HBM once instead of four times.  With a split inner dimension
+  // the tiles of a split read disjoint columns of A, and the plain order (M tiles fastest, spread
+  // over the XCDs) measured faster than grouping a split on one XCD.
+  const int64_t tiles_m = (M - m_base + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  const int64_t splits = (K + k_per_split - 1) / k_per_split;
+  int64_t tile_m, tile_n, split;
+  if (splits == 1) {
+    const int64_t xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    tile_n = local % tiles_n;
+    tile_m = (local / tiles_n) * kXcds + xcd;
+    split = 0;
+    if (tile_m >= tiles_m) return;  // padding of the grid to whole groups of 8
+  } else {
+    const int64_t per = tiles_m * tiles_n, t = blockIdx.x % per;
+    split = blockIdx.x / per;
+    tile_m = t % tiles_m;
+    tile_n = t / tiles_m;
+  }
+  const int64_t m0 = m_base + tile_m * BM;
+  const int64_t n0 = tile_n * BN;
+  const int64_t kb = split * k_per_split;
   const int64_t ke = min(K, kb + k_per_split);
 
   float16v acc[TM][TN];
@@ -235,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
 
   // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
   const bool to_partial = partial != nullptr;
-  float* out = to_partial ? partial + (int64_t)blockIdx.z * M * N : C;
+  float* out = to_partial ? partial + split * M * N : C;
   const int64_t ldo = to_partial ? N : ldc;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -327,9 +349,12 @@ struct GemmArgs {
 template <int BK, bool kFast>
 int launch_rows(const GemmArgs& g, const Shape& s, int64_t m_base, int64_t m_tiles) {
   if (m_tiles <= 0) return MGGCN_OK;
-  MGGCN_REQUIRE(m_tiles < ((int64_t)1 << 31) && s.tiles_n < 65536 && s.splits < 65536, MGGCN_E_OVERFLOW,
-                "GeMM grid %lld x %lld x %d too large", (long long)m_tiles, (long long)s.tiles_n, s.splits);
-  dim3 grid((unsigned)m_tiles, (unsigned)s.tiles_n, (unsigned)s.splits);
+  // unsplit: whole groups of 8 M tiles (one per XCD), the kernel drops the padding
+  const int64_t nblk = s.splits == 1 ? kXcds * ceil_div(m_tiles, kXcds) * s.tiles_n
+                                     : (int64_t)s.splits * m_tiles * s.tiles_n;
+  MGGCN_REQUIRE(nblk < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "GeMM grid of %lld x %lld x %d tiles too large",
+                (long long)m_tiles, (long long)s.tiles_n, s.splits);
+  dim3 grid((unsigned)nblk, 1, 1);
 #define MGGCN_GEMM_LAUNCH(TA, TB)                                                                              \
   gemm_mfma<kBM, kBN, BK, 4, 1, TA, TB, kFast><<<grid, kThreads, 0, g.st>>>(                                   \
       m_base, g.M, g.N, g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, g.beta, g.epi, s.k_per_split, g.partial, g.vecA, \
