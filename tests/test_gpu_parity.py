@@ -633,6 +633,46 @@ def test_adam_step(mg, dev, ref):
         mg.mggcn_adam_step(Wd, Wd, md, vd, 0)
 
 
+def test_training_trajectory(mg, dev, ref):
+    """Ten full training steps (epoch + Adam on every layer) on the tiny configuration, the same ten
+    in the oracle: the loss falls, and the two loss curves stay together.  (Adam's first steps move
+    every weight by about +-lr whatever the size of its gradient, so weights whose gradient is zero
+    to within rounding may step the other way; the comparison is therefore on the loss and on the
+    weights to within a few lr, not per entry to 1e-4.)"""
+    import torch
+
+    cfg = wl.CONFIGS["tiny"]
+    g = cfg.graph()
+    n, dims = g.n_rows, cfg.dims
+    L = len(dims) - 1
+    rp, ci, val = normalized(ref, g)
+    X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=64)
+    model = mg.Model(G, dims)
+    Xd, ld = to_dev(X, dev), to_dev(labels, dev)
+    Wd = [to_dev(w, dev) for w in Ws]
+    md, vd = [torch.zeros_like(w) for w in Wd], [torch.zeros_like(w) for w in Wd]
+    Wr = [w.astype(np.float64) for w in Ws]
+    mr, vr = [np.zeros_like(w) for w in Wr], [np.zeros_like(w) for w in Wr]
+    v64, X64 = val.astype(np.float64), X.astype(np.float64)
+    lr, steps = 0.01, 10
+    gl, rl = [], []
+    for t in range(1, steps + 1):
+        loss, WG = mg.mggcn_epoch(model, Xd, ld, Wd)
+        gl.append(loss.item())
+        r_loss, rWG, _ = ref.epoch(n, rp, ci, v64, X64, labels, Wr)
+        rl.append(r_loss)
+        for l in range(L):
+            mg.mggcn_adam_step(Wd[l], WG[l], md[l], vd[l], t, lr=lr)
+            ref.adam_step(Wr[l], rWG[l], mr[l], vr[l], t, lr=lr)
+    say("[training] gpu losses", [round(x, 5) for x in gl])
+    assert gl[-1] < gl[0] - 0.01 and all(b < a for a, b in zip(gl, gl[1:])), "the loss must fall (labels are random: slowly)"
+    for a, b in zip(gl, rl):
+        assert abs(a - b) <= 2e-4 * abs(b), (gl, rl)
+    for l in range(L):
+        assert np.abs(Wd[l].cpu().numpy() - Wr[l]).max() <= 3 * lr
+
+
 def test_spmm_random_cases(mg, dev, ref):
     """Seeded random small problems: rectangular shapes, random densities, widths, leading
     dimensions, ops, beta, epilogues, segment lengths and panel counts."""
