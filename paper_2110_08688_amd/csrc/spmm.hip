@@ -175,11 +175,11 @@ __global__ __launch_bounds__(kThreads) void spmm_fixup(const FixRow* __restrict_
   }
 }
 
-int launch_any_f32(int vw, int lpr, int gpt, const LaunchArgs& a) {
+int launch_any_f32(int vw, int lpr, const LaunchArgs& a) {
   switch (vw) {
-    case 4: return launch_lpr<float, 4>(lpr, gpt, a);
-    case 2: return launch_lpr<float, 2>(lpr, gpt, a);
-    case 1: return launch_lpr<float, 1>(lpr, gpt, a);
+    case 4: return launch_lpr<float, 4>(lpr, a);
+    case 2: return launch_lpr<float, 2>(lpr, a);
+    case 1: return launch_lpr<float, 1>(lpr, a);
     default: break;
   }
   return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for vector width %d", vw);
@@ -415,16 +415,25 @@ int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts
   for (int32_t p = 0; p < ts.n_panels; ++p) {
     // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
     const int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
+    BinTable& bt = a.bins;
+    bt.n_bins = 0;
+    bt.block_begin[0] = 0;
+    bt.task_begin[0] = 0;
     int64_t begin = 0;
     for (int i = top; i >= 0; --i) {
-      const int64_t end = (i == 0) ? ntasks : ts.cnt_ge[p][i];  // length >= 8 << i  => gpt = 1 << i
+      const int64_t end = (i == 0) ? ntasks : ts.cnt_ge[p][i];  // length >= 8 << i  => 1 << i lane groups
       if (end > begin) {
-        a.tasks = ts.d_tasks + ts.task_begin[p] + begin;
-        a.ntasks = end - begin;
-        const int rc = launch(vw, lpr, 1 << i, a);
-        if (rc) return rc;
+        bt.gpt_log2[bt.n_bins] = i;
+        bt.block_begin[bt.n_bins + 1] = bt.block_begin[bt.n_bins] + spmm_bin_blocks(end - begin, lpr, i, n_chunks);
+        bt.task_begin[bt.n_bins + 1] = end;
+        ++bt.n_bins;
         begin = end;
       }
+    }
+    a.tasks = ts.d_tasks + ts.task_begin[p];
+    if (bt.n_bins > 0) {
+      const int rc = launch(vw, lpr, a);
+      if (rc) return rc;
     }
     const int64_t nfix = ts.fix_begin[(size_t)p + 1] - ts.fix_begin[p];
     if (nfix > 0) {

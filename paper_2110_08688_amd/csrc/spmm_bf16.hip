@@ -9,10 +9,10 @@
 namespace mggcn {
 namespace {
 
-int launch_any_bf16(int vw, int lpr, int gpt, const LaunchArgs& a) {
+int launch_any_bf16(int vw, int lpr, const LaunchArgs& a) {
   switch (vw) {
-    case 8: return launch_lpr<bf16_t, 8>(lpr, gpt, a);
-    case 1: return launch_lpr<bf16_t, 1>(lpr, gpt, a);
+    case 8: return launch_lpr<bf16_t, 8>(lpr, a);
+    case 1: return launch_lpr<bf16_t, 1>(lpr, a);
     default: break;
   }
   return fail(MGGCN_E_UNSUPPORTED, "no bfloat16 SpMM kernel for vector width %d", vw);

@@ -62,10 +62,12 @@ struct Operand<bf16_t, 1> {
   __device__ static inline void fma(float a, const Raw& r, float (&acc)[1]) { acc[0] = fmaf(a, r.v, acc[0]); }
 };
 
+// One workgroup's share of one length bin: `tb` is the workgroup's index inside the bin, `chunk`
+// its feature chunk.
 template <typename XT, int VW, int LPR, int GPT, int UMAX>
-__global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
-    const Task* __restrict__ tasks, int64_t ntasks, const int32_t* __restrict__ colidx,
-    const float* __restrict__ val, const XT* __restrict__ X, uint32_t ldx_bytes, int F, int n_chunks,
+__device__ __forceinline__ void spmm_team_body(
+    int64_t tb, int chunk, const Task* __restrict__ tasks, int64_t ntasks, const int32_t* __restrict__ colidx,
+    const float* __restrict__ val, const XT* __restrict__ X, uint32_t ldx_bytes, int F,
     float beta, int epi, float* __restrict__ Y, int64_t ldy, float* __restrict__ partial,
     int64_t ldp) {
   constexpr int TEAM = LPR * GPT;
@@ -73,8 +75,6 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
   constexpr int U = LPR < UMAX ? LPR : UMAX;
   static_assert(TEAM <= 64 && TPW >= 1, "team must fit a wavefront");
 
-  const int chunk = (int)(blockIdx.x % (unsigned)n_chunks);
-  const int64_t tb = blockIdx.x / (unsigned)n_chunks;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int team = lane / TEAM, tl = lane % TEAM;
   const int g = tl / LPR, fl = tl % LPR;
@@ -187,9 +187,50 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
   }
 }
 
+// The length bins of one pass in one launch.  Tasks are sorted longest first, so a bin (tasks of
+// length >= 8 << i get 1 << i lane groups) is a contiguous range of the task list; workgroups are
+// numbered bin after bin, longest tasks first, and each finds its bin from the workgroup counts.
+// One launch instead of one per bin lets the short tasks fill the tail of the long ones.
+constexpr int kMaxBins = 7;
+struct BinTable {
+  int n_bins;
+  int gpt_log2[kMaxBins];
+  int64_t block_begin[kMaxBins + 1];  // in workgroups, feature chunks included
+  int64_t task_begin[kMaxBins + 1];   // offsets into the pass's task list
+};
+
+template <typename XT, int VW, int LPR, int UMAX>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_tasks(
+    BinTable bins, const Task* __restrict__ tasks, const int32_t* __restrict__ colidx,
+    const float* __restrict__ val, const XT* __restrict__ X, uint32_t ldx_bytes, int F, int n_chunks,
+    float beta, int epi, float* __restrict__ Y, int64_t ldy, float* __restrict__ partial, int64_t ldp) {
+  int b = 0;
+  while (b + 1 < bins.n_bins && (int64_t)blockIdx.x >= bins.block_begin[b + 1]) ++b;
+  const int64_t in_bin = (int64_t)blockIdx.x - bins.block_begin[b];
+  const int chunk = (int)(in_bin % n_chunks);
+  const int64_t tb = in_bin / n_chunks;
+  const Task* t0 = tasks + bins.task_begin[b];
+  const int64_t nt = bins.task_begin[b + 1] - bins.task_begin[b];
+#define MGGCN_SPMM_BIN(G)                                                                                   \
+  if constexpr (LPR * (G) <= 64) {                                                                          \
+    spmm_team_body<XT, VW, LPR, (G), UMAX>(tb, chunk, t0, nt, colidx, val, X, ldx_bytes, F, beta, epi, Y, ldy, \
+                                           partial, ldp);                                                   \
+  }
+  switch (bins.gpt_log2[b]) {  // uniform over the workgroup
+    case 0: MGGCN_SPMM_BIN(1) break;
+    case 1: MGGCN_SPMM_BIN(2) break;
+    case 2: MGGCN_SPMM_BIN(4) break;
+    case 3: MGGCN_SPMM_BIN(8) break;
+    case 4: MGGCN_SPMM_BIN(16) break;
+    case 5: MGGCN_SPMM_BIN(32) break;
+    default: MGGCN_SPMM_BIN(64) break;
+  }
+#undef MGGCN_SPMM_BIN
+}
+
 struct LaunchArgs {
-  const Task* tasks;
-  int64_t ntasks;
+  BinTable bins;      // the length bins of this pass
+  const Task* tasks;  // the pass's task list (device)
   const int32_t* colidx;
   const float* val;
   const void* X;  // float or bfloat16 rows
@@ -204,56 +245,45 @@ struct LaunchArgs {
   hipStream_t stream;
 };
 
-template <typename XT, int VW, int LPR, int GPT>
+// workgroups one bin needs at `lpr` lanes per row: (1 << gpt_log2) lane groups per task
+inline int64_t spmm_bin_blocks(int64_t ntasks, int lpr, int gpt_log2, int n_chunks) {
+  const int64_t teams_per_block = (kSpmmThreads / 64) * (64 / (lpr << gpt_log2));
+  return ceil_div(ntasks, teams_per_block) * n_chunks;
+}
+
+template <typename XT, int VW, int LPR>
 int launch_one(const LaunchArgs& a) {
-  constexpr int TPW = 64 / (LPR * GPT);
-  const int64_t teams_per_block = (kSpmmThreads / 64) * TPW;
-  const int64_t blocks = ceil_div(a.ntasks, teams_per_block) * a.n_chunks;
+  const int64_t blocks = a.bins.block_begin[a.bins.n_bins];
   MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "SpMM grid of %lld blocks too large",
                 (long long)blocks);
-  // 4 gathers per lane in flight: 56 VGPRs, 8 wavefronts per SIMD (8 in flight measured no faster)
-  spmm_tasks<XT, VW, LPR, GPT, 4><<<(unsigned)blocks, kSpmmThreads, 0, a.stream>>>(
-      a.tasks, a.ntasks, a.colidx, a.val, static_cast<const XT*>(a.X), (uint32_t)(a.ldx * (int64_t)sizeof(XT)), a.F, a.n_chunks, a.beta, a.epi, a.Y,
-      a.ldy, a.partial, a.ldp);
+  if (blocks == 0) return MGGCN_OK;
+  // 4 gathers per lane in flight: <= 64 VGPRs, 8 wavefronts per SIMD (8 in flight measured no faster)
+  spmm_tasks<XT, VW, LPR, 4><<<(unsigned)blocks, kSpmmThreads, 0, a.stream>>>(
+      a.bins, a.tasks, a.colidx, a.val, static_cast<const XT*>(a.X), (uint32_t)(a.ldx * (int64_t)sizeof(XT)),
+      a.F, a.n_chunks, a.beta, a.epi, a.Y, a.ldy, a.partial, a.ldp);
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
 }
 
-template <typename XT, int VW, int LPR>
-int launch_gpt(int gpt, const LaunchArgs& a) {
-  switch (gpt) {
-    case 1: return launch_one<XT, VW, LPR, 1>(a);
-    case 2: if constexpr (LPR * 2 <= 64) return launch_one<XT, VW, LPR, 2>(a); break;
-    case 4: if constexpr (LPR * 4 <= 64) return launch_one<XT, VW, LPR, 4>(a); break;
-    case 8: if constexpr (LPR * 8 <= 64) return launch_one<XT, VW, LPR, 8>(a); break;
-    case 16: if constexpr (LPR * 16 <= 64) return launch_one<XT, VW, LPR, 16>(a); break;
-    case 32: if constexpr (LPR * 32 <= 64) return launch_one<XT, VW, LPR, 32>(a); break;
-    case 64: if constexpr (LPR * 64 <= 64) return launch_one<XT, VW, LPR, 64>(a); break;
-    default: break;
-  }
-  return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for %d lanes per row x %d groups", LPR, gpt);
-}
-
 template <typename XT, int VW>
-int launch_lpr(int lpr, int gpt, const LaunchArgs& a) {
+int launch_lpr(int lpr, const LaunchArgs& a) {
   switch (lpr) {
-    case 1: return launch_gpt<XT, VW, 1>(gpt, a);
-    case 2: return launch_gpt<XT, VW, 2>(gpt, a);
-    case 4: return launch_gpt<XT, VW, 4>(gpt, a);
-    case 8: return launch_gpt<XT, VW, 8>(gpt, a);
-    case 16: return launch_gpt<XT, VW, 16>(gpt, a);
-    case 32: return launch_gpt<XT, VW, 32>(gpt, a);
-    case 64: return launch_gpt<XT, VW, 64>(gpt, a);
+    case 1: return launch_one<XT, VW, 1>(a);
+    case 2: return launch_one<XT, VW, 2>(a);
+    case 4: return launch_one<XT, VW, 4>(a);
+    case 8: return launch_one<XT, VW, 8>(a);
+    case 16: return launch_one<XT, VW, 16>(a);
+    case 32: return launch_one<XT, VW, 32>(a);
+    case 64: return launch_one<XT, VW, 64>(a);
     default: break;
   }
   return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for %d lanes per row", lpr);
 }
 
-
-// Runs one SpMM over the graph's task tables (all column panels, all length bins, the fix-up of
-// cut rows) with `launch` starting the kernel for one bin.  Shared by the fp32 and the bfloat16
+// Runs one SpMM over the graph's task tables (all column panels and feature slices, the fix-up of
+// cut rows) with `launch` starting the kernel for one pass.  Shared by the fp32 and the bfloat16
 // entry points; arguments are already checked.
-using SpmmLaunchFn = int (*)(int vw, int lpr, int gpt, const LaunchArgs& a);
+using SpmmLaunchFn = int (*)(int vw, int lpr, const LaunchArgs& a);
 int spmm_run(const mggcn_graph* g, const Orientation& o, const void* X, int64_t ldx, int elem_bytes, int vw,
              int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream, SpmmLaunchFn launch);
 // Argument checks common to both entry points (returns a status, sets the error text).
