@@ -321,7 +321,9 @@ Shape plan_shape(int opA, int64_t M, int64_t N, int64_t K) {
   s.k_per_split = std::max<int64_t>(align_up((size_t)std::max<int64_t>(K, 1), BK), BK);
   if (opA == MGGCN_OP_T && K > 4096) {
     const int64_t tiles = s.tiles_m * s.tiles_n;
-    int64_t want = ceil_div(1024, tiles);  // about four workgroups per CU
+    // all workgroups resident at once: 256 CUs x 4 (a few more would run as a second round
+    // behind the first and double the kernel's time)
+    int64_t want = std::max<int64_t>(1024 / tiles, 1);
     want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
     want = std::max<int64_t>(want, 1);
     s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
