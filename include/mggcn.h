@@ -310,6 +310,8 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
                     int64_t ldhg, int hg_relu_mask, void* stream);
 
 /* One training epoch without the optimiser step: L x layer_fwd, softmax-CE, L x layer_bwd.
+ * Only enqueues kernels on `stream` (no allocation, copy, memset or synchronisation), so the call
+ * may be captured in a HIP graph and replayed.
  * X: n x d_0 (ld ldx).  labels: n int32.  W / W_G: host arrays of L device pointers, W[l]
  * and W_G[l] dense d_l x d_{l+1} (ld = d_{l+1}).  loss_dev: one fp32 on the device.  No
  * gradient with respect to X is formed; the first layer's backward SpMM is kept whenever

@@ -633,6 +633,53 @@ def test_adam_step(mg, dev, ref):
         mg.mggcn_adam_step(Wd, Wd, md, vd, 0)
 
 
+def test_epoch_can_be_captured_in_a_hip_graph(mg, dev, ref):
+    """mggcn_epoch only enqueues kernels on the given stream (no allocation, copy, memset or
+    synchronisation), so a caller may capture it in a HIP graph.  Replayed several times, with eager
+    epochs and synchronisations in between, every replay must give the eager result bit for bit."""
+    import torch
+
+    g = wl.chung_lu(5000, 300e3, 2.1, 2500.0, 8)
+    dims = (50, 128, 41)
+    n = g.n_rows
+    rp, ci, val, X, Ws, labels = _model_inputs(ref, g, dims, 7)
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=128)
+    for flags in (0, mg.MODEL_GATHER_BF16):
+        model = mg.Model(G, dims, flags=flags)
+        Xd, Wd, ld = to_dev(X, dev), [to_dev(w, dev) for w in Ws], to_dev(labels, dev)
+        WG = [torch.empty_like(w) for w in Wd]
+        loss = torch.empty(1, device=dev)
+
+        def step():
+            mg.mggcn_epoch(model, Xd, ld, Wd, W_Gs=WG, loss=loss)
+
+        step()
+        torch.cuda.synchronize()
+        want_loss, want = loss.clone(), [w.clone() for w in WG]
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()  # warm-up on the capture stream
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for r in range(4):
+            for w in WG:
+                w.fill_(float("nan"))
+            loss.fill_(float("nan"))
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(loss, want_loss), f"flags={flags} replay {r}: loss differs"
+            assert all(torch.equal(a, b) for a, b in zip(WG, want)), f"flags={flags} replay {r}: W_G differs"
+            step()  # eager work between replays
+            torch.cuda.synchronize()
+            assert torch.equal(loss, want_loss)
+        del graph
+
+
 def test_training_trajectory(mg, dev, ref):
     """Ten full training steps (epoch + Adam on every layer) on the tiny configuration, the same ten
     in the oracle: the loss falls, and the two loss curves stay together.  (Adam's first steps move
