@@ -177,7 +177,7 @@ int mggcn_graph_panels(const mggcn_graph* g, int op /*mggcn_op*/, int32_t F);
 /* SpMM (Eq. 6 forward, Eq. 9 backward):   Y = epilogue( op(A^) X + beta Y )
  * op N: X is n_cols x F, Y is n_rows x F.  op T: X is n_rows x F, Y is n_cols x F.
  * beta is 0 or 1 (1 = accumulate, the stage loop C^i += A^{ij} H^j of the 1-D row scheme).
- * X and Y must not overlap.  F <= the F_max the graph was bound with.  16-byte aligned
+ * The address ranges of X and Y must not overlap (checked).  F <= the F_max the graph was bound with.  16-byte aligned
  * pointers and leading dimensions that are multiples of 4 take the widest gather path;
  * anything else still works through narrower loads. */
 int mggcn_spmm(const mggcn_graph* g, int op /*mggcn_op*/, const float* X /*dev*/, int64_t ldx,

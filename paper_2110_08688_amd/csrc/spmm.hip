@@ -371,8 +371,8 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
 
 }  // namespace
 
-int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int32_t F, float beta,
-                    int epilogue, const float* Y, int64_t ldy) {
+int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int elem_bytes, int32_t F,
+                    float beta, int epilogue, const float* Y, int64_t ldy) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
   MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
   MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
@@ -391,6 +391,13 @@ int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, in
   if (F == 0 || o.n_rows == 0) return MGGCN_OK;
   MGGCN_REQUIRE(X != nullptr || o.nnz == 0, MGGCN_E_INVALID_ARG, "X is NULL");
   MGGCN_REQUIRE(Y != nullptr, MGGCN_E_INVALID_ARG, "Y is NULL");
+  if (X != nullptr && o.n_cols > 0) {  // rows of Y are written while rows of X are still being gathered
+    const char* xb = static_cast<const char*>(X);
+    const char* xe = xb + ((size_t)(o.n_cols - 1) * (size_t)ldx + (size_t)F) * (size_t)elem_bytes;
+    const char* yb = reinterpret_cast<const char*>(Y);
+    const char* ye = yb + ((size_t)(o.n_rows - 1) * (size_t)ldy + (size_t)F) * sizeof(float);
+    MGGCN_REQUIRE(xe <= yb || ye <= xb, MGGCN_E_INVALID_ARG, "X and Y overlap");
+  }
   return MGGCN_OK;
 }
 
@@ -598,7 +605,7 @@ int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
 
 int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_t F, float beta,
                int epilogue, float* Y, int64_t ldy, void* stream) {
-  int rc = spmm_check_args(g, op, X, ldx, F, beta, epilogue, Y, ldy);
+  int rc = spmm_check_args(g, op, X, ldx, (int)sizeof(float), F, beta, epilogue, Y, ldy);
   if (rc) return rc;
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
   if (F == 0 || o.n_rows == 0) return MGGCN_OK;

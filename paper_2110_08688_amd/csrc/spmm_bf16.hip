@@ -75,7 +75,7 @@ int mggcn_f32_to_bf16(int64_t rows, int32_t cols, const float* src, int64_t lds,
 
 int mggcn_spmm_bf16(const mggcn_graph* g, int op, const uint16_t* X, int64_t ldx, int32_t F, float beta,
                     int epilogue, float* Y, int64_t ldy, void* stream) {
-  const int rc = spmm_check_args(g, op, X, ldx, F, beta, epilogue, Y, ldy);
+  const int rc = spmm_check_args(g, op, X, ldx, (int)sizeof(uint16_t), F, beta, epilogue, Y, ldy);
   if (rc) return rc;
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
   if (F == 0 || o.n_rows == 0) return MGGCN_OK;

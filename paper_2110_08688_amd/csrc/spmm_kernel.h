@@ -287,7 +287,7 @@ using SpmmLaunchFn = int (*)(int vw, int lpr, const LaunchArgs& a);
 int spmm_run(const mggcn_graph* g, const Orientation& o, const void* X, int64_t ldx, int elem_bytes, int vw,
              int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream, SpmmLaunchFn launch);
 // Argument checks common to both entry points (returns a status, sets the error text).
-int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int32_t F, float beta,
-                    int epilogue, const float* Y, int64_t ldy);
+int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, int elem_bytes, int32_t F,
+                    float beta, int epilogue, const float* Y, int64_t ldy);
 
 }  // namespace mggcn

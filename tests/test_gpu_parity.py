@@ -221,6 +221,19 @@ def test_spmm_leading_dimensions_and_padding_untouched(mg, dev, ref, spmm_graphs
     assert np.all(Y[:, F:] == 123.0), "columns beyond F must not be written"
 
 
+def test_spmm_rejects_overlapping_operands(mg, dev, spmm_graphs):
+    import torch
+
+    g, rp, ci, val, G = spmm_graphs["tiny"]
+    buf = torch.zeros((g.n_rows, 64), device=dev)
+    with pytest.raises(mg.MggcnError):
+        mg.mggcn_spmm(G, mg.OP_N, buf[:, :16], Y=buf[:, :16])          # the same rows
+    with pytest.raises(mg.MggcnError):
+        mg.mggcn_spmm(G, mg.OP_N, buf[:, :16], Y=buf[:, 32:48])        # interleaved columns of one buffer
+    other = torch.zeros((g.n_rows, 16), device=dev)
+    mg.mggcn_spmm(G, mg.OP_N, buf[:, :16], Y=other)                    # disjoint: fine
+
+
 @pytest.mark.parametrize("name", ["adversarial", "powerlaw"])
 @pytest.mark.parametrize("F", [16, 100])
 def test_spmm_accumulate_and_epilogues(mg, dev, ref, spmm_graphs, name, F):
