@@ -128,8 +128,9 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * Graph handle: A^ in CSR, optionally A^^T in CSR, and the one-time load-balancing analysis
  * the SpMM uses (rows cut into segments of bounded length, segments ordered longest first).
  *
- * _create reads rowptr (and rowptr_t) back to the host, SYNCHRONISES the stream, and builds
- * the segment tables on the host.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the
+ * _create reads rowptr (and rowptr_t) back to the host, finds on the device where every row
+ * crosses the column-panel boundaries (a few bytes per row, written to pinned host memory it
+ * allocates and frees itself), SYNCHRONISES the stream, and builds the segment tables on the host.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the
  * case for the symmetric normalisation of an undirected graph); op T then runs on A^ itself.
  * The CSR arrays are borrowed, not copied: they must outlive the handle.
  * seg_len = maximum entries per segment (0 = library default).

@@ -41,23 +41,46 @@ namespace {
 constexpr int kThreads = kSpmmThreads;
 constexpr int kDefaultSegLen = 2048;
 
-// Row-segment tables for `n_panels` column panels.  colidx (host copy) is only needed when
-// n_panels > 1.
-void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vector<int64_t>& rowptr,
-                    const int32_t* colidx, int32_t n_panels, int32_t seg_len) {
+// Entry offset at which each row crosses each panel boundary: cuts[i * n_cuts + c] = first entry
+// of row i whose column is >= (c + 1) * width (columns are ascending inside a row).  One thread per
+// (row, boundary), a binary search each; written straight into pinned host memory, so the host
+// never needs a copy of the column indices.
+template <typename IT>
+__global__ __launch_bounds__(kSpmmThreads) void panel_cuts(int32_t n_rows, int32_t n_cols, const IT* __restrict__ rowptr,
+                                                            const int32_t* __restrict__ colidx, int64_t width,
+                                                            int32_t n_cuts, uint32_t* __restrict__ cuts) {
+  const int64_t idx = (int64_t)blockIdx.x * kSpmmThreads + threadIdx.x;
+  if (idx >= (int64_t)n_rows * n_cuts) return;
+  const int64_t i = idx / n_cuts;
+  const int32_t c = (int32_t)(idx % n_cuts);
+  const int64_t bound = min((int64_t)(c + 1) * width, (int64_t)n_cols);
+  int64_t lo = rowptr[i], hi = rowptr[i + 1];
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (colidx[mid] < bound) lo = mid + 1; else hi = mid;
+  }
+  cuts[idx] = (uint32_t)lo;
+}
+
+// Row-segment tables for `n_panels` column panels, in two passes over the rows: count the tasks
+// of every (panel, length), turn the counts into the positions of a longest-first counting sort,
+// then write every task to its final place (row order is kept inside a length).
+// cuts: per row `cut_stride` boundary offsets (see panel_cuts) of which every `cut_step`-th is a
+// boundary of this table's panels; unused (may be NULL) for a single panel.
+void build_task_set(TaskSet* ts, int32_t n_rows, const std::vector<int64_t>& rowptr, const uint32_t* cuts,
+                    int32_t cut_stride, int32_t cut_step, int32_t n_panels, int32_t seg_len) {
   const int32_t P = std::max(n_panels, 1);
-  const int64_t width = ceil_div(std::max(n_cols, 1), P);
   ts->n_panels = P;
-  std::vector<std::vector<Task>> per_panel((size_t)P);
-  std::vector<std::vector<FixRow>> per_panel_fix((size_t)P);
-  std::vector<int64_t> slots((size_t)P, 0);
+  const size_t L = (size_t)seg_len + 1;                       // lengths 0 .. seg_len
+  std::vector<int64_t> pos((size_t)P * L, 0);                 // [panel][seg_len - length]
+  std::vector<int64_t> n_fix((size_t)P, 0), slots((size_t)P, 0);
   std::vector<int64_t> cut((size_t)P + 1);
-  for (int32_t i = 0; i < n_rows; ++i) {
-    const int64_t b = rowptr[i], e = rowptr[(size_t)i + 1];
-    cut[0] = b;
-    cut[(size_t)P] = e;
-    for (int32_t p = 1; p < P; ++p)
-      cut[p] = (int64_t)(std::lower_bound(colidx + cut[p - 1], colidx + e, (int32_t)std::min<int64_t>(p * width, n_cols)) - colidx);
+
+  // calls emit(panel, k0, len, flags, slot) for every task of row i, fix(panel, nseg, flags) for every cut row
+  auto walk_row = [&](int32_t i, auto&& emit, auto&& fix) {
+    cut[0] = rowptr[i];
+    cut[(size_t)P] = rowptr[(size_t)i + 1];
+    for (int32_t p = 1; p < P; ++p) cut[p] = (int64_t)cuts[(size_t)i * cut_stride + (size_t)p * cut_step - 1];
     int32_t first = -1, last = -1;
     for (int32_t p = 0; p < P; ++p)
       if (cut[(size_t)p + 1] > cut[p]) { if (first < 0) first = p; last = p; }
@@ -68,51 +91,56 @@ void build_task_set(TaskSet* ts, int32_t n_rows, int32_t n_cols, const std::vect
       if (len == 0 && !(p == first && first == last)) continue;
       const uint32_t flags = (p == first ? kTaskFirst : 0u) | (p == last ? kTaskLast : 0u);
       if (len <= seg_len) {
-        per_panel[p].push_back({i, (uint32_t)lo, (uint32_t)len | flags, -1});
+        emit(p, lo, len, flags, -1);
       } else {
         const int32_t nseg = (int32_t)ceil_div(len, seg_len);
         const int32_t piece = (int32_t)ceil_div(len, nseg);
-        per_panel_fix[p].push_back({i, (int32_t)slots[p], nseg, flags});
+        fix(p, nseg, flags);
         for (int32_t s = 0; s < nseg; ++s) {
           const int64_t k0 = lo + (int64_t)s * piece;
           const int64_t k1 = std::min<int64_t>(lo + len, k0 + piece);
-          per_panel[p].push_back({i, (uint32_t)k0, (uint32_t)(k1 - k0), (int32_t)slots[p]++});
+          emit(p, k0, (int32_t)(k1 - k0), 0u, 0);  // slot number assigned by the caller
         }
       }
     }
-  }
-  ts->tasks.clear();
-  ts->fix.clear();
+  };
+
+  for (int32_t i = 0; i < n_rows; ++i)
+    walk_row(i, [&](int32_t p, int64_t, int32_t len, uint32_t, int32_t) { ++pos[(size_t)p * L + (size_t)(seg_len - len)]; },
+             [&](int32_t p, int32_t nseg, uint32_t) { ++n_fix[p]; slots[p] += nseg; });
+
   ts->task_begin.assign((size_t)P + 1, 0);
   ts->fix_begin.assign((size_t)P + 1, 0);
   ts->cnt_ge.assign((size_t)P, {});
   ts->n_slots = 0;
-  std::vector<int64_t> start;
+  int64_t run = 0;
   for (int32_t p = 0; p < P; ++p) {
-    const std::vector<Task>& in = per_panel[p];
-    // counting sort by length, longest first, row order kept inside a length
-    start.assign((size_t)seg_len + 2, 0);
-    for (const Task& t : in) start[(size_t)(seg_len - (int32_t)(t.len_flags & kTaskLenMask)) + 1]++;
-    for (int32_t l = 0; l <= seg_len; ++l) start[(size_t)l + 1] += start[l];
-    const size_t base = ts->tasks.size();
-    ts->tasks.resize(base + in.size());
-    for (const Task& t : in)
-      ts->tasks[base + (size_t)start[(size_t)(seg_len - (int32_t)(t.len_flags & kTaskLenMask))]++] = t;
-    for (int i = 0; i < kLenClasses; ++i) {
-      const uint32_t thr = 8u << i;
-      int64_t lo = 0, hi = (int64_t)in.size();  // descending lengths: count of length >= thr
-      while (lo < hi) {
-        const int64_t mid = (lo + hi) / 2;
-        if ((ts->tasks[base + (size_t)mid].len_flags & kTaskLenMask) >= thr) lo = mid + 1; else hi = mid;
-      }
-      ts->cnt_ge[p][i] = lo;
+    const int64_t base = run;
+    for (size_t l = 0; l < L; ++l) {  // l = seg_len - length: descending lengths
+      const int64_t c = pos[(size_t)p * L + l];
+      pos[(size_t)p * L + l] = run;
+      run += c;
+      const int64_t len = (int64_t)seg_len - (int64_t)l;
+      for (int k = 0; k < kLenClasses; ++k)
+        if (len >= (8 << k)) ts->cnt_ge[p][k] = run - base;  // tasks of this panel at least that long
     }
-    ts->task_begin[(size_t)p + 1] = (int64_t)ts->tasks.size();
-    ts->fix.insert(ts->fix.end(), per_panel_fix[p].begin(), per_panel_fix[p].end());
-    ts->fix_begin[(size_t)p + 1] = (int64_t)ts->fix.size();
+    ts->task_begin[(size_t)p + 1] = run;
+    ts->fix_begin[(size_t)p + 1] = ts->fix_begin[p] + n_fix[p];
     ts->n_slots = std::max(ts->n_slots, slots[p]);
-    std::vector<Task>().swap(per_panel[p]);
   }
+  ts->tasks.assign((size_t)run, Task{0, 0u, 0u, -1});
+  ts->fix.assign((size_t)ts->fix_begin[(size_t)P], FixRow{0, 0, 0, 0u});
+  std::vector<int64_t> fix_at(ts->fix_begin.begin(), ts->fix_begin.end() - 1);
+  std::fill(slots.begin(), slots.end(), 0);
+  for (int32_t i = 0; i < n_rows; ++i)
+    walk_row(i,
+             [&](int32_t p, int64_t k0, int32_t len, uint32_t flags, int32_t slot) {
+               if (slot >= 0) slot = (int32_t)slots[p]++;
+               ts->tasks[(size_t)pos[(size_t)p * L + (size_t)(seg_len - len)]++] = {i, (uint32_t)k0, (uint32_t)len | flags, slot};
+             },
+             [&](int32_t p, int32_t nseg, uint32_t flags) {
+               ts->fix[(size_t)fix_at[p]++] = {i, (int32_t)slots[p], nseg, flags};
+             });
 }
 
 int pow2_floor(int64_t x) {
@@ -340,17 +368,29 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
     MGGCN_REQUIRE(o->nnz < ((int64_t)1 << 32), MGGCN_E_OVERFLOW,
                   "%lld entries: entry offsets are held in 32 unsigned bits", (long long)o->nnz);
     MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
-    build_task_set(&o->flat, nr, nc, h, nullptr, 1, seg_len);
+    build_task_set(&o->flat, nr, h, nullptr, 0, 0, 1, seg_len);
     const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
-    if (Pmax > 1) {
-      // panel cuts need the column indices: one read-back, setup only
-      std::vector<int32_t> hc((size_t)o->nnz);
-      MGGCN_HIP(hipMemcpyAsync(hc.data(), ci, sizeof(int32_t) * (size_t)o->nnz, hipMemcpyDeviceToHost, s));
-      MGGCN_HIP(hipStreamSynchronize(s));
+    if (Pmax > 1 && nr > 0) {
+      // Where every row crosses the panel boundaries is found on the device and lands in pinned
+      // host memory; the panel forms for fewer panels use every 2nd, 4th, ... of the same cuts
+      // (an automatic set has power-of-two panel counts over one common finest width).
+      const int32_t n_cuts = Pmax - 1;
+      const int64_t width = ceil_div(std::max(nc, 1), Pmax);
+      uint32_t* cuts = nullptr;
+      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&cuts), sizeof(uint32_t) * (size_t)nr * (size_t)n_cuts, hipHostMallocDefault));
+      const int64_t items = (int64_t)nr * n_cuts;
+      panel_cuts<IT><<<(unsigned)ceil_div(items, kThreads), kThreads, 0, s>>>(nr, nc, rp, ci, width, n_cuts, cuts);
+      hipError_t e = hipGetLastError();
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      if (e != hipSuccess) {
+        (void)hipHostFree(cuts);
+        return fail(MGGCN_E_HIP, "panel boundary search failed: %s", hipGetErrorString(e));
+      }
       for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
         o->panelled.emplace_back();
-        build_task_set(&o->panelled.back(), nr, nc, h, hc.data(), P, seg_len);
+        build_task_set(&o->panelled.back(), nr, h, cuts, n_cuts, Pmax / P, P, seg_len);
       }
+      MGGCN_HIP(hipHostFree(cuts));
     }
     // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
     // and lose the shared panel), so it is built only on request.
