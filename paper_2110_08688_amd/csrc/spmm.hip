@@ -1,7 +1,7 @@
 // CSR SpMM  Y = epilogue( op(A^) X + beta Y )  for gfx950 -- the product that takes most of a
 // GCN epoch (Eq. 6 forward, Eq. 9 backward of the paper).
 //
-// Work decomposition (done once per graph on the host, the graph being fixed for all epochs):
+// Work decomposition (done once per graph, the graph being fixed for all epochs):
 //   every row is cut into segments of at most seg_len entries; a segment is a task.  Tasks are
 //   ordered longest first.  A row with one segment is written straight to Y; the segments of a
 //   cut row go to a partial-sum table and a second small kernel adds them in segment order, so
@@ -14,19 +14,20 @@
 // a (row, panel) pair are a contiguous sub-range, so no data moves.  Panels run as successive
 // launches on the stream, each adding into Y (beta = 1 after a row's first panel, epilogue at its
 // last): all wavefronts in flight then gather from the same 1/P of X.  The price is one
-// read-modify-write of Y per panel, so P is capped by the average row length.
+// read-modify-write of Y per panel, so P is capped by the average row length.  Tables are kept
+// for P = 2, 4, 8, ... and each product picks the count that brings one panel of its operand to
+// about 16 MiB; an operand too wide even for the largest count is also walked in feature slices.
 //
-// Kernel mapping (wave64):
-//   the feature dimension runs along lanes: LPR lanes x VW floats cover one feature chunk of a
+// Kernel mapping (wave64), see spmm_kernel.h:
+//   the feature dimension runs along lanes: LPR lanes x VW elements cover one feature chunk of a
 //   dense row, so a gathered row is read with 16-byte loads that are contiguous across lanes.
 //   A team of LPR*GPT lanes owns one task: GPT lane groups walk the segment's entries
 //   interleaved, and their accumulators are folded with xor-shuffles at the end.  Column
 //   indices and values are fetched TEAM entries at a time with one coalesced streaming load
 //   and handed to the groups by ds_bpermute.  Long tasks get the whole wave (GPT = 64/LPR);
-//   short ones get narrower teams so that several rows share a wave.
-//   Feature chunks map to blockIdx so that, with 2, 4 or 8 chunks, one chunk always lands on the
-//   same XCDs (workgroups are dealt round-robin over the 8 XCDs): each L2 then caches a
-//   1/n_chunks column slice of X instead of all of it.
+//   short ones get narrower teams so that several rows share a wave; all length bins of a pass
+//   run in one launch.  A row wider than one wave's reach (more than 64 lanes x VW elements)
+//   is covered by several feature chunks, interleaved over blockIdx.
 #include "spmm_kernel.h"
 
 #include <algorithm>
