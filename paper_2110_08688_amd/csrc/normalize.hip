@@ -216,8 +216,9 @@ int normalize_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr_in, const in
   if (rc) return rc;
   MGGCN_REQUIRE(mode == MGGCN_NORM_SYM_SELFLOOP || mode == MGGCN_NORM_MEAN_IN, MGGCN_E_INVALID_ARG,
                 "unknown normalisation mode %d", mode);
-  MGGCN_REQUIRE(rowptr_out && colidx_out && val_out, MGGCN_E_INVALID_ARG,
-                "rowptr_out / colidx_out / val_out is NULL");
+  MGGCN_REQUIRE(rowptr_out != nullptr, MGGCN_E_INVALID_ARG, "rowptr_out is NULL");
+  if (n_rows == 0 || n_cols == 0) return MGGCN_OK;  // no entries: nothing to fill (outputs may be NULL)
+  MGGCN_REQUIRE(colidx_out && val_out, MGGCN_E_INVALID_ARG, "colidx_out / val_out is NULL");
   MGGCN_REQUIRE(!(mode == MGGCN_NORM_SYM_SELFLOOP && n_rows != n_cols && (!deg_row || !deg_col)),
                 MGGCN_E_INVALID_ARG,
                 "symmetric normalisation of a rectangular %d x %d block needs deg_row and deg_col",

@@ -221,6 +221,56 @@ def test_spmm_leading_dimensions_and_padding_untouched(mg, dev, ref, spmm_graphs
     assert np.all(Y[:, F:] == 123.0), "columns beyond F must not be written"
 
 
+def test_spmm_degenerate_shapes(mg, dev, ref):
+    """no rows, no columns of features, a single vertex, one row holding every entry (cut into many
+    segments, in single-pass and in panelled form), a matrix with no entries at all"""
+    import torch
+
+    # no rows / a single isolated vertex
+    for n in (0, 1):
+        rp = np.zeros(n + 1, np.int32)
+        ci = np.zeros(0, np.int32)
+        grp, gci, gval = mg.mggcn_csr_normalize(n, n, to_dev(rp, dev), to_dev(ci, dev))
+        assert gci.numel() == n and (n == 0 or gval.item() == 1.0)
+        G = mg.Graph(n, n, grp, gci, gval, F_max=8)
+        Y = mg.mggcn_spmm(G, mg.OP_N, torch.ones((n, 8), device=dev))
+        assert Y.shape == (n, 8) and (n == 0 or bool((Y == 1.0).all()))
+    # F = 0 is a no-op
+    g = wl.CONFIGS["tiny"].graph()
+    rp, ci, val = normalized(ref, g)
+    G = mg.Graph(g.n_rows, g.n_cols, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=16)
+    mg.mggcn_spmm(G, mg.OP_N, torch.zeros((g.n_rows, 16), device=dev), F=0, Y=torch.zeros((g.n_rows, 16), device=dev))
+    # a matrix without entries: Y = beta * Y, epilogue applied
+    n = 300
+    z = mg.Graph(n, n, to_dev(np.zeros(n + 1, np.int32), dev), to_dev(np.zeros(0, np.int32), dev),
+                 to_dev(np.zeros(0, np.float32), dev), F_max=8)
+    Y0 = wl.normal_f32(1, 1, (n, 8))
+    Yd = to_dev(Y0, dev)
+    mg.mggcn_spmm(z, mg.OP_N, torch.ones((n, 8), device=dev), beta=1.0, epilogue=mg.EPI_RELU, Y=Yd)
+    assert np.array_equal(Yd.cpu().numpy(), np.maximum(Y0, 0.0))
+    mg.mggcn_spmm(z, mg.OP_N, torch.ones((n, 8), device=dev), Y=Yd)
+    assert bool((Yd == 0).all())
+    # one row with every entry: 60,000 entries -> 30 segments of a cut row; the other rows are empty
+    n, m, F = 5, 60000, 24
+    rp = np.array([0, 0, m, m, m, m], np.int32)
+    ci = np.arange(m, dtype=np.int32)
+    va = wl.normal_f32(2, 1, (m,))
+    X = wl.normal_f32(2, 2, (m, F))
+    want = ref.spmm(ref.OP_N, n, m, rp, ci, va.astype(np.float64), X.astype(np.float64))
+    scale = np.abs(va).astype(np.float64) @ np.abs(X).astype(np.float64)
+    d = [to_dev(a, dev) for a in (rp, ci, va)]
+    t = mg.mggcn_csr_transpose(n, m, *d)
+    for P in (0, 1, 5):
+        G = mg.Graph(n, m, *d, transpose=t, F_max=F, n_panels=P)
+        got = mg.mggcn_spmm(G, mg.OP_N, to_dev(X, dev)).cpu().numpy()
+        assert np.all(got[[0, 2, 3, 4]] == 0)
+        assert np.all(np.abs(got[1] - want[1]) <= 1e-5 * scale.max()), f"P={P}"
+        # the transposed operator: every output row is one entry times one row of the operand
+        R = wl.normal_f32(2, 3, (n, F))
+        got_t = mg.mggcn_spmm(G, mg.OP_T, to_dev(R, dev)).cpu().numpy()
+        np.testing.assert_allclose(got_t, va[:, None].astype(np.float64) * R[1][None, :], rtol=1e-6, atol=0)
+
+
 def test_spmm_rejects_overlapping_operands(mg, dev, spmm_graphs):
     import torch
 
