@@ -467,6 +467,29 @@ def test_gemm_tn_split_k(mg, dev, ref, M, N, K):
     assert np.array_equal(a, b), "split-K reduction must be reproducible"
 
 
+def test_gemm_degenerate_shapes(mg, dev, ref):
+    """empty outputs are no-ops; an empty inner dimension leaves epilogue(beta * C)"""
+    import torch
+
+    A = torch.ones((0, 5), device=dev)
+    B = torch.ones((5, 7), device=dev)
+    assert mg.mggcn_gemm(mg.OP_N, mg.OP_N, A, B).shape == (0, 7)
+    assert mg.mggcn_gemm(mg.OP_N, mg.OP_N, torch.ones((4, 5), device=dev), torch.ones((5, 0), device=dev)).shape == (4, 0)
+    C0 = wl.normal_f32(9, 1, (37, 11))
+    for beta, epi, want in [(0.0, mg.EPI_NONE, np.zeros_like(C0)), (1.0, mg.EPI_NONE, C0),
+                            (1.0, mg.EPI_RELU, np.maximum(C0, 0.0))]:
+        Cd = to_dev(C0, dev)
+        mg.mggcn_gemm(mg.OP_N, mg.OP_N, torch.ones((37, 0), device=dev), torch.ones((0, 11), device=dev), beta=beta,
+                      epilogue=epi, Cm=Cd)
+        assert np.array_equal(Cd.cpu().numpy(), want), (beta, epi)
+    # a single element, and a single row times a wide matrix
+    one = mg.mggcn_gemm(mg.OP_N, mg.OP_N, torch.full((1, 1), 3.0, device=dev), torch.full((1, 1), -2.0, device=dev))
+    assert one.item() == -6.0
+    a, b = wl.normal_f32(9, 2, (1, 300)), wl.normal_f32(9, 3, (300, 513))
+    got = mg.mggcn_gemm(mg.OP_N, mg.OP_N, to_dev(a, dev), to_dev(b, dev)).cpu().numpy()
+    assert_rows_close(got, ref.gemm(ref.OP_N, ref.OP_N, a.astype(np.float64), b.astype(np.float64)), what="1 x 513")
+
+
 def test_gemm_epilogues_beta_and_strides(mg, dev, ref):
     import torch
 
