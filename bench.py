@@ -268,6 +268,15 @@ def main() -> int:
     dom_bytes = spmm_bytes(nnz, n, Fdom)
     achieved = dom_bytes / (dom_ms * 1e-3) / 1e9
     P = graph.panels(Fdom)
+    # compulsory bytes (every gathered row fetched once) and the time the better of the two ceilings allows
+    bytes_min = 8 * nnz + 4 * (n + 1) + 4 * Fdom * n + 4 * Fdom * n
+    t_min_ms = max(bytes_min / (HBM_PEAK_GBPS * 1e9), 2.0 * nnz * Fdom / (FP32_MFMA_PEAK_TFLOPS * 1e12)) * 1e3
+    # what a plain device copy reaches on this machine (1 GiB each way), for scale next to the 8 TB/s figure
+    ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+    cb = torch.empty_like(ca)
+    copy_ms = timed(lambda: cb.copy_(ca), 5)[1]
+    copy_gbps = 2.0 * ca.numel() * 4 / (copy_ms * 1e-3) / 1e9
+    del ca, cb
     roofline = {
         "kernel": f"spmm_tasks<VW=4,LPR={min(64, 1 << max(0, (Fdom + 3) // 4 - 1).bit_length())},...>: one mggcn_spmm "
                   f"call at F={Fdom} = {P} launches of it, one per pass over the entries (column panels x feature slices; "
@@ -282,6 +291,9 @@ def main() -> int:
         "avg_launch_ms": round(dom_ms / P, 4),
         "call_ms_mean": round(dom_ms, 4), "call_ms_min": round(ops[f"spmm_fwd_l{ldom}_F{Fdom}"][1], 4),
         "gflops": round(2.0 * nnz * Fdom / (dom_ms * 1e-3) / 1e9, 1),
+        "compulsory_bytes_per_call": bytes_min, "t_min_ms": round(t_min_ms, 4),
+        "t_min_over_t": round(t_min_ms / dom_ms, 4),
+        "device_copy_GBps": round(copy_gbps, 1), "achieved_over_device_copy": round(achieved / copy_gbps, 4),
         "note": "achieved counts algorithmic bytes (no reuse of gathered rows); most gathers are served "
                 "by L2 / Infinity Cache, so a fraction above 1 is cache reuse, not HBM bandwidth",
     }
