@@ -141,7 +141,9 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * 1 = never; > 1 = always that many).
  * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
  * also holds the partial sums of rows that were cut, for feature widths up to F_max.
- * A handle may be re-bound; it must be bound before mggcn_spmm is called.
+ * A handle may be re-bound; it must be bound before mggcn_spmm is called.  Products on one handle
+ * share its partial-sum table: enqueue them on one stream (or otherwise keep them from
+ * overlapping in time); use one handle per stream for concurrent products.
  * ---------------------------------------------------------------------------------------- */
 typedef struct mggcn_graph mggcn_graph;
 
