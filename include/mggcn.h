@@ -253,7 +253,8 @@ int mggcn_adam_step(int64_t count, float* W, const float* G, float* m, float* v,
  *
  * dims: host array of L+1 widths d_0..d_L.  orders: host array of L mggcn_order values or
  * NULL (= AUTO everywhere).  The graph must be square, bound with F_max >= every SpMM
- * width the model needs (mggcn_model_spmm_width_max), and outlive the model.
+ * width the model needs (mggcn_model_spmm_width_max), and outlive the model.  Calls on one model
+ * use its arena (and its graph's tables): keep them on one stream.
  * ---------------------------------------------------------------------------------------- */
 typedef struct mggcn_model mggcn_model;
 
