@@ -72,12 +72,84 @@ def spmm_sweep(args, cfg, mg, torch, dev) -> int:
     return 0
 
 
+def block_layer(args, cfg, mg, torch, dev) -> int:
+    """One GPU's share of a 1-D row partition (the rectangular 13.9M x 111M block): the 128 -> 256 layer
+    forward and backward, SpMM first, as the sequence of calls mggcn_layer_fwd / _bwd make on a square
+    graph.  The gradient with respect to the dense operand (A^^T U, 111M x 128) is included.  Left
+    out: the other seven row blocks and every exchange between GPUs."""
+    import numpy as np
+
+    t0 = time.time()
+    g = cfg.graph()
+    nr, nc = g.n_rows, g.n_cols
+    deg_row = (np.diff(g.rowptr) + 1).astype(np.int32)                     # stand-in global degrees
+    deg_col = (1 + 8 * np.bincount(g.colidx, minlength=nc)).astype(np.int32)
+    gen_s = time.time() - t0
+    rowptr, colidx, val = mg.mggcn_csr_normalize(nr, nc, torch.from_numpy(g.rowptr).to(dev), torch.from_numpy(g.colidx).to(dev),
+                                                 deg_row=torch.from_numpy(deg_row).to(dev), deg_col=torch.from_numpy(deg_col).to(dev))
+    nnz = int(colidx.numel())
+    t = mg.mggcn_csr_transpose(nr, nc, rowptr, colidx, val)
+    d_in, d_out = cfg.dims
+    graph = mg.Graph(nr, nc, rowptr, colidx, val, transpose=t, F_max=d_in, seg_len=args.seg_len)
+    gen = torch.Generator(device=dev).manual_seed(cfg.seed + 0x100)
+    X = torch.randn((nc, d_in), device=dev, generator=gen)
+    W = torch.from_numpy(cfg.weights()[0]).to(dev)
+    G = torch.randn((nr, d_out), device=dev, generator=gen)
+    P = torch.empty((nr, d_in), device=dev)
+    H = torch.empty((nr, d_out), device=dev)
+    U = torch.empty((nr, d_in), device=dev)
+    XG = torch.empty((nc, d_in), device=dev)
+    WG = torch.empty_like(W)
+
+    def timed(fn, reps):
+        fn()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in evs:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = [a.elapsed_time(b) for a, b in evs]
+        return float(np.mean(ts)), float(np.min(ts))
+
+    reps = max(3, args.steps)
+    ops = {
+        f"spmm_fwd_F{d_in}": timed(lambda: mg.mggcn_spmm(graph, mg.OP_N, X, Y=P), reps),
+        f"gemm_fwd_{d_in}x{d_out}": timed(lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, P, W, epilogue=mg.EPI_RELU, Cm=H), reps),
+        "gemm_wgrad": timed(lambda: mg.mggcn_gemm(mg.OP_T, mg.OP_N, P, G, Cm=WG), reps),
+        "gemm_hgrad": timed(lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_T, G, W, Cm=U), reps),
+        f"spmm_bwd_F{d_in}": timed(lambda: mg.mggcn_spmm(graph, mg.OP_T, U, Y=XG), reps),
+    }
+    fwd_b = spmm_bytes(nnz, nr, d_in)
+    bwd_b = spmm_bytes(nnz, nc, d_in)
+    fwd_ms, bwd_ms = ops[f"spmm_fwd_F{d_in}"][0], ops[f"spmm_bwd_F{d_in}"][0]
+    gemm_ms = sum(v[0] for k, v in ops.items() if k.startswith("gemm"))
+    step_ms = sum(v[0] for v in ops.values())
+    out = {
+        "metric": "spmm_effective_bandwidth", "value": round((fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": reps, "warmup": 1, "ms_per_step": round(step_ms, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"block: one GPU's 1/8 row block of a Papers-shaped graph, {nr} x {nc}, nnz={nnz} (with "
+                               f"diagonal), layer {d_in}->{d_out} forward + backward (SpMM first), sum of the five calls"},
+        "spmm_pct_hbm_roofline": round(100.0 * (fwd_b + bwd_b) / ((fwd_ms + bwd_ms) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "gemm_tflops": round(3 * 2.0 * nr * d_in * d_out / (gemm_ms * 1e-3) / 1e12, 2),
+        "ops_ms_mean_min": {k: [round(v[0], 4), round(v[1], 4)] for k, v in ops.items()},
+        "generate_s": round(gen_s, 3),
+        "roofline": {"kernel": f"spmm_tasks<float,4,32,4>: forward product at F={d_in}, one launch", "bound": "hbm",
+                     "achieved": round(fwd_b / (fwd_ms * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(fwd_b / (fwd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4), "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large", "rmat", "proteins"])
+    ap.add_argument("--config", default="medium", choices=["tiny", "medium", "large", "rmat", "proteins", "block"])
     ap.add_argument("--spmm-sweep", default="", metavar="F1,F2,...",
                     help="feature-width sweep mode: time the forward SpMM of the chosen configuration's graph at "
                          "each width (HIP events, min of 10), print one JSON object, then exit")
@@ -112,6 +184,8 @@ def main() -> int:
 
     if args.spmm_sweep:
         return spmm_sweep(args, cfg, mg, torch, dev)
+    if args.config == "block":
+        return block_layer(args, cfg, mg, torch, dev)
 
     t0 = time.time()
     g = cfg.graph()
