@@ -162,7 +162,7 @@ def main() -> int:
                     help="with --profile-spmm: the feature width to run at (default: the epoch's widest SpMM)")
     ap.add_argument("--profile-gemm", type=int, default=0, metavar="N",
                     help="counter-collection mode: N calls of the first layer's forward GeMM (H W with the padded "
-                         "leading dimension the epoch uses), then exit")
+                         "leading dimension the epoch uses) and N of its weight-gradient GeMM, then exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
@@ -230,6 +230,9 @@ def main() -> int:
         out = torch.empty((n, (dims[1] + 15) // 16 * 16), device=dev)[:, :dims[1]]
         for _ in range(args.profile_gemm):
             mg.mggcn_gemm(mg.OP_N, mg.OP_N, X, Ws[0], Cm=out)
+        wg = torch.empty_like(Ws[0])
+        for _ in range(args.profile_gemm):  # the same layer's weight gradient: inner dimension = vertex count, split
+            mg.mggcn_gemm(mg.OP_T, mg.OP_N, X, out, Cm=wg)
         torch.cuda.synchronize()
         print(json.dumps({"mode": "profile-gemm", "calls": args.profile_gemm, "M": n, "N": dims[1], "K": dims[0],
                           "lda": int(X.stride(0)), "flop_per_call": 2 * n * dims[0] * dims[1]}))
