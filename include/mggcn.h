@@ -39,7 +39,8 @@ typedef enum {
   MGGCN_E_OVERFLOW = -3,    /* a size does not fit the int32 index type                    */
   MGGCN_E_WORKSPACE = -4,   /* workspace missing, too small or misaligned (256 B)          */
   MGGCN_E_HIP = -5,         /* a HIP runtime call failed (message holds hipGetErrorString)  */
-  MGGCN_E_UNSUPPORTED = -6  /* valid request this build does not implement                 */
+  MGGCN_E_UNSUPPORTED = -6, /* valid request this build does not implement                 */
+  MGGCN_E_NO_MEMORY = -7    /* host memory for the library's own tables could not be had    */
 } mggcn_status;
 
 /* Which normalisation mggcn_csr_normalize applies to the pattern A~ = A united with I. */

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmggcn.so")
 
 OK = 0
-E_INVALID_ARG, E_BAD_CSR, E_OVERFLOW, E_WORKSPACE, E_HIP, E_UNSUPPORTED = -1, -2, -3, -4, -5, -6
+E_INVALID_ARG, E_BAD_CSR, E_OVERFLOW, E_WORKSPACE, E_HIP, E_UNSUPPORTED, E_NO_MEMORY = -1, -2, -3, -4, -5, -6, -7
 NORM_SYM_SELFLOOP, NORM_MEAN_IN = 0, 1
 OP_N, OP_T = 0, 1
 EPI_NONE, EPI_RELU, EPI_RELU_MASK = 0, 1, 2

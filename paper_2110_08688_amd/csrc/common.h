@@ -7,6 +7,8 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <exception>
+#include <new>
 
 #include "../../include/mggcn.h"
 
@@ -35,6 +37,18 @@ int fail(int code, const char* fmt, ...);
       return ::mggcn::fail(MGGCN_E_HIP, "kernel launch failed at %s:%d: %s", __FILE__, __LINE__, \
                            hipGetErrorString(e_));                                            \
   } while (0)
+
+// Body of an entry point that builds host-side tables: a C caller never sees a C++ exception.
+template <class Fn>
+int guarded(Fn&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return fail(MGGCN_E_NO_MEMORY, "out of host memory");
+  } catch (const std::exception& e) {
+    return fail(MGGCN_E_NO_MEMORY, "host-side failure: %s", e.what());
+  }
+}
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

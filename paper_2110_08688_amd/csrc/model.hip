@@ -30,6 +30,7 @@ struct mggcn_model {
   bool cache_valid = false;
   bool gather_bf16 = false;  // every SpMM gathers a bfloat16 copy of its operand
   size_t off_bf16 = 0;       // that copy: n x padded_ld(widest SpMM) 2-byte elements
+  int32_t bf16_width = 0;    // the widest SpMM operand it was sized for
 };
 
 namespace mggcn {
@@ -96,51 +97,56 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
       MGGCN_REQUIRE(orders[l] >= MGGCN_ORDER_AUTO && orders[l] <= MGGCN_ORDER_SPMM_FIRST,
                     MGGCN_E_INVALID_ARG, "orders[%d] = %d is not an mggcn_order", l, orders[l]);
   mggcn_model* m = new (std::nothrow) mggcn_model;
-  MGGCN_REQUIRE(m != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
-  m->g = g;
-  m->n = g->fwd.n_rows;
-  m->L = L;
-  m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
-  m->gather_bf16 = (flags & MGGCN_MODEL_GATHER_BF16) != 0;
-  m->dims.assign(dims, dims + L + 1);
-  m->orders.resize(L);
-  m->ld_act.resize(L);
-  m->off_act.resize(L);
-  m->off_p.assign(L, (size_t)-1);
-  m->ld_p.assign(L, 0);
-  const size_t n = (size_t)std::max(m->n, 1);
-  size_t off = 0;
-  int32_t tmp_width = 1;
-  for (int32_t l = 0; l < L; ++l) {
-    m->orders[l] = resolve_order(dims[l], dims[l + 1], orders ? orders[l] : MGGCN_ORDER_AUTO);
-    if (l == 0 && m->cache_input) m->orders[l] = MGGCN_ORDER_SPMM_FIRST;  // its A^ H buffer is the cache
-    m->ld_act[l] = padded_ld(dims[l + 1]);
-    m->off_act[l] = off;
-    off += align_up(n * (size_t)m->ld_act[l] * sizeof(float), kWsAlign);
-    if (m->orders[l] == MGGCN_ORDER_SPMM_FIRST) {
-      m->ld_p[l] = padded_ld(dims[l]);
-      m->off_p[l] = off;
-      off += align_up(n * (size_t)m->ld_p[l] * sizeof(float), kWsAlign);
-      if (!(l == 0 && m->cache_input)) tmp_width = std::max(tmp_width, dims[l]);
-    } else {
-      tmp_width = std::max(tmp_width, dims[l + 1]);
+  MGGCN_REQUIRE(m != nullptr, MGGCN_E_NO_MEMORY, "out of host memory");
+  const int rc = guarded([&]() -> int {
+    m->g = g;
+    m->n = g->fwd.n_rows;
+    m->L = L;
+    m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
+    m->gather_bf16 = (flags & MGGCN_MODEL_GATHER_BF16) != 0;
+    m->dims.assign(dims, dims + L + 1);
+    m->orders.resize(L);
+    m->ld_act.resize(L);
+    m->off_act.resize(L);
+    m->off_p.assign(L, (size_t)-1);
+    m->ld_p.assign(L, 0);
+    const size_t n = (size_t)std::max(m->n, 1);
+    size_t off = 0;
+    int32_t tmp_width = 1;
+    for (int32_t l = 0; l < L; ++l) {
+      m->orders[l] = resolve_order(dims[l], dims[l + 1], orders ? orders[l] : MGGCN_ORDER_AUTO);
+      if (l == 0 && m->cache_input) m->orders[l] = MGGCN_ORDER_SPMM_FIRST;  // its A^ H buffer is the cache
+      m->ld_act[l] = padded_ld(dims[l + 1]);
+      m->off_act[l] = off;
+      off += align_up(n * (size_t)m->ld_act[l] * sizeof(float), kWsAlign);
+      if (m->orders[l] == MGGCN_ORDER_SPMM_FIRST) {
+        m->ld_p[l] = padded_ld(dims[l]);
+        m->off_p[l] = off;
+        off += align_up(n * (size_t)m->ld_p[l] * sizeof(float), kWsAlign);
+        if (!(l == 0 && m->cache_input)) tmp_width = std::max(tmp_width, dims[l]);
+      } else {
+        tmp_width = std::max(tmp_width, dims[l + 1]);
+      }
+      m->gemm_ws_bytes = std::max(
+          m->gemm_ws_bytes, mggcn_gemm_workspace_bytes(MGGCN_OP_T, MGGCN_OP_N, dims[l], dims[l + 1], m->n));
     }
-    m->gemm_ws_bytes = std::max(
-        m->gemm_ws_bytes, mggcn_gemm_workspace_bytes(MGGCN_OP_T, MGGCN_OP_N, dims[l], dims[l + 1], m->n));
-  }
-  m->off_tmp = off;
-  off += align_up(n * (size_t)padded_ld(tmp_width) * sizeof(float), kWsAlign);
-  if (m->gather_bf16) {
-    const int32_t w = mggcn_model_spmm_width_max(dims, m->orders.data(), L, flags);
-    m->off_bf16 = off;
-    off += align_up(n * (size_t)padded_ld(w) * sizeof(uint16_t), kWsAlign);
-  }
-  m->off_gemm_ws = off;
-  off += align_up(m->gemm_ws_bytes, kWsAlign);
-  m->loss_ws_bytes = mggcn_softmax_ce_workspace_bytes(m->n);
-  m->off_loss_ws = off;
-  off += align_up(m->loss_ws_bytes, kWsAlign);
-  m->arena_bytes = off + kWsAlign;
+    m->off_tmp = off;
+    off += align_up(n * (size_t)padded_ld(tmp_width) * sizeof(float), kWsAlign);
+    if (m->gather_bf16) {
+      const int32_t w = mggcn_model_spmm_width_max(dims, m->orders.data(), L, flags);
+      m->off_bf16 = off;
+      m->bf16_width = w;
+      off += align_up(n * (size_t)padded_ld(w) * sizeof(uint16_t), kWsAlign);
+    }
+    m->off_gemm_ws = off;
+    off += align_up(m->gemm_ws_bytes, kWsAlign);
+    m->loss_ws_bytes = mggcn_softmax_ce_workspace_bytes(m->n);
+    m->off_loss_ws = off;
+    off += align_up(m->loss_ws_bytes, kWsAlign);
+    m->arena_bytes = off + kWsAlign;
+    return MGGCN_OK;
+  });
+  if (rc) { delete m; return rc; }
   *out = m;
   return MGGCN_OK;
 }
@@ -193,7 +199,8 @@ int mggcn_model_gather_operand(const mggcn_model* m, int32_t width, uint16_t** p
   MGGCN_REQUIRE(m != nullptr && ptr_out && ld_out, MGGCN_E_INVALID_ARG, "model / ptr_out / ld_out is NULL");
   MGGCN_REQUIRE(m->gather_bf16, MGGCN_E_INVALID_ARG, "model was created without MGGCN_MODEL_GATHER_BF16");
   MGGCN_REQUIRE(m->arena != nullptr, MGGCN_E_WORKSPACE, "model is not bound to an arena");
-  MGGCN_REQUIRE(width >= 1, MGGCN_E_INVALID_ARG, "width %d must be positive", width);
+  MGGCN_REQUIRE(width >= 1 && width <= m->bf16_width, MGGCN_E_INVALID_ARG,
+                "width %d outside [1, %d], the widths of this model's SpMM operands", width, m->bf16_width);
   *ptr_out = reinterpret_cast<uint16_t*>(m->arena + m->off_bf16);
   *ld_out = padded_ld(width);
   return MGGCN_OK;

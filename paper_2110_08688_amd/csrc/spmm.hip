@@ -332,7 +332,7 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
   hipStream_t s = as_stream(stream);
 
   mggcn_graph* g = new (std::nothrow) mggcn_graph;
-  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "out of host memory");
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_NO_MEMORY, "out of host memory");
   g->symmetric = (rowptr_t == nullptr);
   g->seg_len = seg_len;
   g->panel_bytes = 16ll << 20;
@@ -377,21 +377,21 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
       // (an automatic set has power-of-two panel counts over one common finest width).
       const int32_t n_cuts = Pmax - 1;
       const int64_t width = ceil_div(std::max(nc, 1), Pmax);
-      uint32_t* cuts = nullptr;
-      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&cuts), sizeof(uint32_t) * (size_t)nr * (size_t)n_cuts, hipHostMallocDefault));
+      struct Pinned {  // freed on every way out, a failed allocation of the tables included
+        uint32_t* p = nullptr;
+        ~Pinned() { if (p) (void)hipHostFree(p); }
+      } pinned;
+      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&pinned.p), sizeof(uint32_t) * (size_t)nr * (size_t)n_cuts, hipHostMallocDefault));
+      uint32_t* cuts = pinned.p;
       const int64_t items = (int64_t)nr * n_cuts;
       panel_cuts<IT><<<(unsigned)ceil_div(items, kThreads), kThreads, 0, s>>>(nr, nc, rp, ci, width, n_cuts, cuts);
       hipError_t e = hipGetLastError();
       if (e == hipSuccess) e = hipStreamSynchronize(s);
-      if (e != hipSuccess) {
-        (void)hipHostFree(cuts);
-        return fail(MGGCN_E_HIP, "panel boundary search failed: %s", hipGetErrorString(e));
-      }
+      if (e != hipSuccess) return fail(MGGCN_E_HIP, "panel boundary search failed: %s", hipGetErrorString(e));
       for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
         o->panelled.emplace_back();
         build_task_set(&o->panelled.back(), nr, h, cuts, n_cuts, Pmax / P, P, seg_len);
       }
-      MGGCN_HIP(hipHostFree(cuts));
     }
     // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
     // and lose the shared panel), so it is built only on request.
@@ -399,8 +399,8 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
       return build_sweep_for(o, default_sweep_panels(nc), default_sweep_rows(), s);
     return MGGCN_OK;
   };
-  int rc = setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val);
-  if (!rc && !g->symmetric) rc = setup(&g->bwd, n_cols, n_rows, rowptr_t, colidx_t, val_t);
+  int rc = guarded([&] { return setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val); });
+  if (!rc && !g->symmetric) rc = guarded([&] { return setup(&g->bwd, n_cols, n_rows, rowptr_t, colidx_t, val_t); });
   if (!rc && !g->symmetric)
     if (g->bwd.nnz != g->fwd.nnz)
       rc = fail(MGGCN_E_BAD_CSR, "transpose has %lld entries, matrix has %lld",
@@ -553,7 +553,9 @@ int mggcn_graph_create64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr, 
 
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max) {
   if (!g || F_max < 0) return 0;
-  return carve_graph(g, F_max, nullptr, nullptr);
+  size_t bytes = 0;
+  const int rc = guarded([&] { bytes = carve_graph(g, F_max, nullptr, nullptr); return (int)MGGCN_OK; });
+  return rc ? 0 : bytes;
 }
 
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, void* stream) {
@@ -561,51 +563,54 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
   MGGCN_REQUIRE(F_max >= 1, MGGCN_E_INVALID_ARG, "F_max = %d must be positive", F_max);
   MGGCN_REQUIRE(ws && aligned(ws, kWsAlign), MGGCN_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   const size_t need = mggcn_graph_workspace_bytes(g, F_max);
+  MGGCN_REQUIRE(need > 0, MGGCN_E_NO_MEMORY, "out of host memory while sizing the workspace");
   MGGCN_REQUIRE(ws_bytes >= need, MGGCN_E_WORKSPACE, "workspace too small: %zu bytes given, %zu needed",
                 ws_bytes, need);
   hipStream_t s = as_stream(stream);
-  GraphCarve gc;
-  carve_graph(g, F_max, ws, &gc);
-  Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
-  for (int o = 0; o < 2; ++o) {
-    if (!os[o]) continue;
-    std::vector<TaskSet*> sets = {&os[o]->flat};
-    for (TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
-    for (size_t k = 0; k < sets.size(); ++k) {
-      TaskSet* ts = sets[k];
-      ts->d_tasks = gc.tasks[o][k];
-      ts->d_fix = gc.fix[o][k];
-      if (!ts->tasks.empty())
-        MGGCN_HIP(hipMemcpyAsync(ts->d_tasks, ts->tasks.data(), sizeof(Task) * ts->tasks.size(),
-                                 hipMemcpyHostToDevice, s));
-      if (!ts->fix.empty())
-        MGGCN_HIP(hipMemcpyAsync(ts->d_fix, ts->fix.data(), sizeof(FixRow) * ts->fix.size(),
-                                 hipMemcpyHostToDevice, s));
+  return guarded([&]() -> int {
+    GraphCarve gc;
+    carve_graph(g, F_max, ws, &gc);
+    Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
+    for (int o = 0; o < 2; ++o) {
+      if (!os[o]) continue;
+      std::vector<TaskSet*> sets = {&os[o]->flat};
+      for (TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
+      for (size_t k = 0; k < sets.size(); ++k) {
+        TaskSet* ts = sets[k];
+        ts->d_tasks = gc.tasks[o][k];
+        ts->d_fix = gc.fix[o][k];
+        if (!ts->tasks.empty())
+          MGGCN_HIP(hipMemcpyAsync(ts->d_tasks, ts->tasks.data(), sizeof(Task) * ts->tasks.size(),
+                                   hipMemcpyHostToDevice, s));
+        if (!ts->fix.empty())
+          MGGCN_HIP(hipMemcpyAsync(ts->d_fix, ts->fix.data(), sizeof(FixRow) * ts->fix.size(),
+                                   hipMemcpyHostToDevice, s));
+      }
     }
-  }
-  for (int o = 0; o < 2; ++o) {
-    if (!os[o] || os[o]->sweep.n_panels == 0) continue;
-    SweepSet& sw = os[o]->sweep;
-    sw.d_scol = gc.sweep[o].scol; sw.d_sval = gc.sweep[o].sval; sw.d_team_begin = gc.sweep[o].team_begin;
-    sw.d_slot_row = gc.sweep[o].slot_row; sw.d_slot_out = gc.sweep[o].slot_out; sw.d_fix = gc.sweep[o].fix;
-    auto up = [&](void* dst, const void* src, size_t bytes) -> int {
-      if (bytes) MGGCN_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
-      return MGGCN_OK;
-    };
-    int rc = up(sw.d_scol, sw.scol.data(), sizeof(uint32_t) * sw.scol.size());
-    if (!rc) rc = up(sw.d_sval, sw.sval.data(), sizeof(float) * sw.sval.size());
-    if (!rc) rc = up(sw.d_team_begin, sw.team_begin.data(), sizeof(int32_t) * sw.team_begin.size());
-    if (!rc) rc = up(sw.d_slot_row, sw.slot_row.data(), sizeof(int32_t) * sw.slot_row.size());
-    if (!rc) rc = up(sw.d_slot_out, sw.slot_out.data(), sizeof(int32_t) * sw.slot_out.size());
-    if (!rc) rc = up(sw.d_fix, sw.fix.data(), sizeof(FixRow) * sw.fix.size());
-    if (rc) return rc;
-  }
-  MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
-  g->d_partial = gc.partial;
-  g->ldp = gc.ldp;
-  g->F_bound = F_max;
-  g->bound = true;
-  return MGGCN_OK;
+    for (int o = 0; o < 2; ++o) {
+      if (!os[o] || os[o]->sweep.n_panels == 0) continue;
+      SweepSet& sw = os[o]->sweep;
+      sw.d_scol = gc.sweep[o].scol; sw.d_sval = gc.sweep[o].sval; sw.d_team_begin = gc.sweep[o].team_begin;
+      sw.d_slot_row = gc.sweep[o].slot_row; sw.d_slot_out = gc.sweep[o].slot_out; sw.d_fix = gc.sweep[o].fix;
+      auto up = [&](void* dst, const void* src, size_t bytes) -> int {
+        if (bytes) MGGCN_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
+        return MGGCN_OK;
+      };
+      int rc = up(sw.d_scol, sw.scol.data(), sizeof(uint32_t) * sw.scol.size());
+      if (!rc) rc = up(sw.d_sval, sw.sval.data(), sizeof(float) * sw.sval.size());
+      if (!rc) rc = up(sw.d_team_begin, sw.team_begin.data(), sizeof(int32_t) * sw.team_begin.size());
+      if (!rc) rc = up(sw.d_slot_row, sw.slot_row.data(), sizeof(int32_t) * sw.slot_row.size());
+      if (!rc) rc = up(sw.d_slot_out, sw.slot_out.data(), sizeof(int32_t) * sw.slot_out.size());
+      if (!rc) rc = up(sw.d_fix, sw.fix.data(), sizeof(FixRow) * sw.fix.size());
+      if (rc) return rc;
+    }
+    MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
+    g->d_partial = gc.partial;
+    g->ldp = gc.ldp;
+    g->F_bound = F_max;
+    g->bound = true;
+    return MGGCN_OK;
+  });
 }
 
 int mggcn_graph_destroy(mggcn_graph* g) {
@@ -624,8 +629,10 @@ int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_t
   Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
   for (int o = 0; o < 2; ++o) {
     if (!os[o]) continue;
-    const int rc = build_sweep_for(os[o], n_panels > 0 ? n_panels : default_sweep_panels(os[o]->n_cols),
-                                   rows_per_team > 0 ? rows_per_team : default_sweep_rows(), s);
+    const int rc = guarded([&] {
+      return build_sweep_for(os[o], n_panels > 0 ? n_panels : default_sweep_panels(os[o]->n_cols),
+                             rows_per_team > 0 ? rows_per_team : default_sweep_rows(), s);
+    });
     if (rc) return rc;
   }
   g->sweep_forced = true;
@@ -636,6 +643,7 @@ int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_t
 int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
   MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
+  MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
   const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes;
   if (o.sweep.n_panels > 0 && (g->sweep_forced || big)) return 1;  // sweep form: one launch

@@ -403,6 +403,11 @@ def test_model_bf16_flag_errors(mg, dev, ref):
         plain.gather_operand(16)
     with pytest.raises(mg.MggcnError):
         mg.Model(G, (64, 16, 8), flags=64)
+    half = mg.Model(G, (64, 16, 8), flags=mg.MODEL_GATHER_BF16)  # GeMM first twice: SpMM widths 16 and 8
+    assert half.gather_operand(16).shape == (g.n_rows, 16)
+    for width in (0, 17, 64):  # the copy holds the widest SpMM operand, nothing wider
+        with pytest.raises(mg.MggcnError):
+            half.gather_operand(width)
 
 
 @pytest.mark.parametrize("F", [100, 256, 602])
