@@ -12,7 +12,7 @@ import ctypes as C
 from . import binding as B
 from .binding import (  # noqa: F401  (re-exported constants)
     EPI_NONE, EPI_RELU, EPI_RELU_MASK, NORM_MEAN_IN, NORM_SYM_SELFLOOP, OP_N, OP_T, ORDER_AUTO,
-    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MODEL_CACHE_INPUT, MODEL_GATHER_BF16, MggcnError,
+    ORDER_GEMM_FIRST, ORDER_SPMM_FIRST, MODEL_CACHE_INPUT, MODEL_GATHER_BF16, MODEL_GEMM_BF16X3, MggcnError,
 )
 
 
@@ -176,7 +176,7 @@ def mggcn_spmm_bf16(graph: Graph, op, Xb, F=None, beta=0.0, epilogue=EPI_NONE, Y
 # GeMM, ReLU', loss
 # ------------------------------------------------------------------------------------------
 
-def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None):
+def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None, entry="mggcn_gemm"):
     torch = _torch()
     L = B.lib()
     M = A.shape[0] if opA == OP_N else A.shape[1]
@@ -186,11 +186,17 @@ def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=Non
         Cm = torch.empty((M, N), dtype=torch.float32, device=A.device)
     nbytes = L.mggcn_gemm_workspace_bytes(opA, opB, M, N, K)
     ws = _ws(nbytes, A.device) if nbytes else None
-    B.check(L.mggcn_gemm(opA, opB, M, N, K, B.ptr(A), B.ld_of(A), B.ptr(Bm), B.ld_of(Bm), float(beta), epilogue,
-                         B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, nbytes, _stream(stream)))
+    B.check(getattr(L, entry)(opA, opB, M, N, K, B.ptr(A), B.ld_of(A), B.ptr(Bm), B.ld_of(Bm), float(beta), epilogue,
+                              B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, nbytes,
+                              _stream(stream)))
     if ws is not None and stream is None:
         torch.cuda.current_stream().synchronize()
     return Cm
+
+
+def mggcn_gemm_bf16x3(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None):
+    """The same product on the bfloat16 matrix instructions (three exact pieces per operand)."""
+    return mggcn_gemm(opA, opB, A, Bm, beta=beta, epilogue=epilogue, Cm=Cm, stream=stream, entry="mggcn_gemm_bf16x3")
 
 
 def mggcn_relu_bwd(act, G, stream=None):

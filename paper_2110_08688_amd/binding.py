@@ -18,7 +18,7 @@ NORM_SYM_SELFLOOP, NORM_MEAN_IN = 0, 1
 OP_N, OP_T = 0, 1
 EPI_NONE, EPI_RELU, EPI_RELU_MASK = 0, 1, 2
 ORDER_AUTO, ORDER_GEMM_FIRST, ORDER_SPMM_FIRST = -1, 0, 1
-MODEL_CACHE_INPUT, MODEL_GATHER_BF16 = 1, 2
+MODEL_CACHE_INPUT, MODEL_GATHER_BF16, MODEL_GEMM_BF16X3 = 1, 2, 4
 
 _vp, _i32, _i64, _sz, _f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
 
@@ -45,6 +45,8 @@ SIGNATURES = {
     "mggcn_f32_to_bf16": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),
     "mggcn_gemm_workspace_bytes": (_sz, [C.c_int, C.c_int, _i64, _i64, _i64]),
     "mggcn_gemm": (C.c_int, [C.c_int, C.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _f32, C.c_int, _vp, _i64,
+                             _vp, _sz, _vp]),
+    "mggcn_gemm_bf16x3": (C.c_int, [C.c_int, C.c_int, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _f32, C.c_int, _vp, _i64,
                              _vp, _sz, _vp]),
     "mggcn_relu_bwd": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),
     "mggcn_adam_step": (C.c_int, [_i64, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _f32, _f32, _vp]),

@@ -79,4 +79,9 @@ int exclusive_scan_i32(const int32_t* counts, int64_t n, int32_t* out, int32_t* 
 // The same with 64-bit offsets (totals beyond 2^31); tmp needs scan_tmp_ints(n) int64 entries.
 int exclusive_scan_i64(const int32_t* counts, int64_t n, int64_t* out, int64_t* tmp, hipStream_t s);
 
+// The GeMM behind mggcn_gemm (pieces = false) and mggcn_gemm_bf16x3 (pieces = true).
+int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+             const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
+             size_t ws_bytes, void* stream);
+
 }  // namespace mggcn

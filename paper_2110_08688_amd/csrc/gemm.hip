@@ -148,6 +148,64 @@ __device__ inline float gemm_epilogue(float acc, float old, float beta, int epi)
   return acc;
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.  The
+// 1-D grid is therefore decoded so that the N tiles of one M tile -- they re-read the same rows
+// of A -- sit on one XCD next to each other in time.  Measured on 2.45M x 256 x 256: 3.33 ->
+// 2.91 ms, A being fetched from HBM once instead of four times.  With a split inner dimension
+// the tiles of a split read disjoint columns of A, and the plain order (M tiles fastest, spread
+// over the XCDs) measured faster than grouping a split on one XCD.
+// Returns false for a workgroup that only pads the grid to whole groups of 8.
+__device__ inline bool decode_tile(int64_t m_rows, int64_t N, int64_t K, int bm, int bn, int64_t k_per_split,
+                                   int64_t* tile_m, int64_t* tile_n, int64_t* split) {
+  const int64_t tiles_m = (m_rows + bm - 1) / bm, tiles_n = (N + bn - 1) / bn;
+  const int64_t splits = (K + k_per_split - 1) / k_per_split;
+  if (splits == 1) {
+    const int64_t xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+    *tile_n = local % tiles_n;
+    *tile_m = (local / tiles_n) * kXcds + xcd;
+    *split = 0;
+    return *tile_m < tiles_m;
+  }
+  const int64_t per = tiles_m * tiles_n, t = blockIdx.x % per;
+  *split = blockIdx.x / per;
+  *tile_m = t % tiles_m;
+  *tile_n = t / tiles_m;
+  return true;
+}
+
+// The TM x TN accumulator tiles of one wavefront, whose corner is (row0, col0), go to C (with the
+// epilogue) or to this split's partial product.  Accumulator register r of lane l is
+// C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile.
+template <int TM, int TN>
+__device__ inline void store_tiles(const float16v (&acc)[TM][TN], int64_t row0, int64_t col0, bool whole, int64_t M,
+                                   int64_t N, int64_t split, float* __restrict__ C, int64_t ldc, float beta,
+                                   int epi, float* __restrict__ partial) {
+  const int lane = threadIdx.x & 63;
+  const int frow = lane >> 5, fcol = lane & 31;
+  const bool to_partial = partial != nullptr;
+  float* out = to_partial ? partial + split * M * N : C;
+  const int64_t ldo = to_partial ? N : ldc;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int64_t col = col0 + j * 32 + fcol;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = row0 + i * 32 + 8 * (r / 4) + 4 * frow + (r % 4);
+        if (whole || (row < M && col < N)) {
+          float* dst = out + row * ldo + col;
+          if (to_partial) {
+            *dst = acc[i][j][r];
+          } else {
+            const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
+            *dst = gemm_epilogue(acc[i][j][r], old, beta, epi);
+          }
+        }
+      }
+    }
+}
+
 // WM x WN wavefronts tile the BM x BN block; each wavefront holds TM x TN accumulators of 32x32.
 // kFast: the host guarantees 16-byte aligned operands and whole tiles along N, so a block whose
 // M tile is whole loads its full k-steps with no checks at all (measured +15 %); the ragged last
@@ -176,27 +234,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave / WN, wn = wave % WN;
-  // Workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own L2.  The
-  // 1-D grid is therefore decoded so that the N tiles of one M tile -- they re-read the same rows
-  // of A -- sit on one XCD next to each other in time.  Measured on 2.45M x 256 x 256: 3.33 ->
-  // 2.91 ms, A being fetched from HBM once instead of four times.  With a split inner dimension
-  // the tiles of a split read disjoint columns of A, and the plain order (M tiles fastest, spread
-  // over the XCDs) measured faster than grouping a split on one XCD.
-  const int64_t tiles_m = (M - m_base + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-  const int64_t splits = (K + k_per_split - 1) / k_per_split;
   int64_t tile_m, tile_n, split;
-  if (splits == 1) {
-    const int64_t xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-    tile_n = local % tiles_n;
-    tile_m = (local / tiles_n) * kXcds + xcd;
-    split = 0;
-    if (tile_m >= tiles_m) return;  // padding of the grid to whole groups of 8
-  } else {
-    const int64_t per = tiles_m * tiles_n, t = blockIdx.x % per;
-    split = blockIdx.x / per;
-    tile_m = t % tiles_m;
-    tile_n = t / tiles_m;
-  }
+  if (!decode_tile(M - m_base, N, K, BM, BN, k_per_split, &tile_m, &tile_n, &split)) return;
   const int64_t m0 = m_base + tile_m * BM;
   const int64_t n0 = tile_n * BN;
   const int64_t kb = split * k_per_split;
@@ -255,29 +294,220 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
     __syncthreads();
   }
 
-  // accumulator register r of lane l is C[8*(r/4) + 4*(l/32) + r%4][l%32] of its 32x32 tile
-  const bool to_partial = partial != nullptr;
-  float* out = to_partial ? partial + split * M * N : C;
-  const int64_t ldo = to_partial ? N : ldc;
+  store_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, whole, M, N, split, C, ldc, beta, epi, partial);
+}
+
+
+// ---------------------------------------------------------------------------------------
+// fp32 products out of bfloat16 matrix instructions
+// ---------------------------------------------------------------------------------------
+// An fp32 number is the exact sum of three bfloat16 numbers: its upper 16 bits, the upper 16 bits
+// of what that leaves, and the rest (24 significand bits = 3 x 8, every difference exact).  With
+// a = a0 + a1 + a2 and b = b0 + b1 + b2 the product a b is the sum of nine piece products, each of
+// which the bf16 matrix instruction forms exactly and adds in fp32.  With |a1| < 2^-7 |a| and
+// |a2| < 2^-15 |a| (2^-8 and 2^-16 on average) the three smallest, a1 b2 + a2 b1 + a2 b2, stay
+// below 2^-21 |a b| (about 2^-24 |a b| on average: one fp32 rounding of the product) and are
+// dropped; unlike the rounding of the running sum, which fp32 arithmetic of any kind pays at
+// every one of the K additions, this error does not grow with K.  The other six are added
+// smallest first.  Six v_mfma_f32_32x32x16_bf16 do the
+// work of eight v_mfma_f32_32x32x2_f32 in a quarter of their time, so the product runs at up to
+// 2.6x the fp32 matrix rate; the price is the split itself (5.5 vector operations per element
+// staged, done once per tile) and 1.5x the LDS traffic.
+// Non-finite inputs: a piece of Inf is Inf and leaves Inf - Inf, so an Inf operand yields NaN where
+// fp32 arithmetic yields Inf; NaN stays NaN.  Values below 2^-110 lose their lower pieces to the
+// subnormal flush of the matrix unit (absolute error below 2^-126 per product).
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kPieceBK = 32;
+// 80-byte rows: the 16-byte fragment reads of 32 consecutive rows fall on distinct banks, and so
+// do the 8-byte stores of the loaders (two rows of 64 bytes per 32 lanes)
+constexpr int kPieceLd = kPieceBK + 8;
+
+// upper halves of two words: (lo >> 16) | (hi & 0xffff0000)
+__device__ inline uint32_t upper_halves(uint32_t hi, uint32_t lo) { return __builtin_amdgcn_perm(hi, lo, 0x07060302u); }
+
+// Four values that follow each other along k, cut into their three pieces and stored as four
+// bfloat16 per piece plane at S[plane][row][k4 .. k4+3].
+template <int R>
+__device__ inline void store_pieces(uint16_t (*S)[R][kPieceLd], int row, int k4, float x0, float x1, float x2,
+                                    float x3) {
+  const float x[4] = {x0, x1, x2, x3};
+  uint32_t top[4], mid[4], low[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    top[i] = __float_as_uint(x[i]);
+    const float r1 = x[i] - __uint_as_float(top[i] & 0xffff0000u);  // exact: at most 16 significant bits left
+    mid[i] = __float_as_uint(r1);
+    const float r2 = r1 - __uint_as_float(mid[i] & 0xffff0000u);    // exact: at most 8 left, a bfloat16 as it is
+    low[i] = __float_as_uint(r2);
+  }
+  *reinterpret_cast<uint2*>(&S[0][row][k4]) = make_uint2(upper_halves(top[1], top[0]), upper_halves(top[3], top[2]));
+  *reinterpret_cast<uint2*>(&S[1][row][k4]) = make_uint2(upper_halves(mid[1], mid[0]), upper_halves(mid[3], mid[2]));
+  *reinterpret_cast<uint2*>(&S[2][row][k4]) = make_uint2(upper_halves(low[1], low[0]), upper_halves(low[3], low[2]));
+}
+
+// Staging of a tile whose memory rows run along K (see KContig, whose loads are used): thread
+// (row r, k-quad kq) of each pass holds four consecutive k of one row.
+template <int R>
+__device__ inline void store_pieces_kcontig(uint16_t (*S)[R][kPieceLd], const float (&reg)[KContig<R, kPieceBK>::kRegs]) {
+  using L = KContig<R, kPieceBK>;
+  const int r = threadIdx.x / L::kThreadsPerRow, kq = threadIdx.x % L::kThreadsPerRow;
+#pragma unroll
+  for (int p = 0; p < L::kPasses; ++p)
+    store_pieces<R>(S, p * L::kRowsPerPass + r, 4 * kq, reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]);
+}
+
+// Tile of an operand whose memory rows run along the tile's M/N side, 32 x R: a thread takes a
+// 4 x 4 block -- four consecutive k (one load each) of four consecutive columns -- so that after
+// the transposition in registers every column again has four consecutive k to store.  Lanes run
+// along k first (8 groups of 4), then along the column quads: one load instruction reads eight
+// whole 128-byte lines.  R / 4 * 8 threads take part.
+template <int R>
+struct MContigK4 {
+  static constexpr int kUsed = R / 4 * 8;
+  static constexpr int kRegs = 16;
+  static_assert(kUsed <= kThreads, "tile wider than the workgroup can stage");
+  template <bool kFast>
+  __device__ static inline void load(const float* __restrict__ src, int64_t ld, int64_t col0, int64_t col_end,
+                                     int64_t k0, int64_t k_end, int vec, float (&reg)[kRegs]) {
+    const int kg = threadIdx.x % 8, cq = threadIdx.x / 8;
+    if (kUsed < kThreads && threadIdx.x >= kUsed) return;
+    const int64_t col = col0 + 4 * cq;
+    const bool interior = kFast || (col0 + R <= col_end && k0 + kPieceBK <= k_end);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int64_t k = k0 + 4 * kg + p;
+      const float* ptr = src + k * ld + col;
+      if (interior && vec == 4) {
+        const float4 t = *reinterpret_cast<const float4*>(ptr);
+        reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+      } else if (interior && vec == 2) {
+        const float2 t = *reinterpret_cast<const float2*>(ptr);
+        const float2 u = *reinterpret_cast<const float2*>(ptr + 2);
+        reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = u.x; reg[p * 4 + 3] = u.y;
+      } else if (interior) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) reg[p * 4 + i] = ptr[i];
+      } else if (vec == 4 && k < k_end && col + 3 < col_end) {
+        const float4 t = *reinterpret_cast<const float4*>(ptr);
+        reg[p * 4 + 0] = t.x; reg[p * 4 + 1] = t.y; reg[p * 4 + 2] = t.z; reg[p * 4 + 3] = t.w;
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) reg[p * 4 + i] = (k < k_end && col + i < col_end) ? ptr[i] : 0.f;
+      }
+    }
+  }
+  __device__ static inline void store(uint16_t (*S)[R][kPieceLd], const float (&reg)[kRegs]) {
+    const int kg = threadIdx.x % 8, cq = threadIdx.x / 8;
+    if (kUsed < kThreads && threadIdx.x >= kUsed) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      store_pieces<R>(S, 4 * cq + i, 4 * kg, reg[0 * 4 + i], reg[1 * 4 + i], reg[2 * 4 + i], reg[3 * 4 + i]);
+  }
+};
+
+// BM x BN tile of C by 2 x 2 wavefronts, k-steps of 32.  Both operand tiles sit in LDS as three
+// planes of bfloat16 pieces, [row or column][k] with k contiguous: lane l of a 32x32x16 matrix
+// instruction feeds row (column) l % 32 with the eight k that start at 8 * (l / 32), one 16-byte
+// read.  A and B use the same k numbering, so the product does not depend on it.  Two workgroups
+// share a CU (60 KB of LDS, at most 256 registers each).
+// kFast: as for the fp32 kernel.
+template <int BM, int BN, bool TA, bool TB, bool kFast>
+__global__ __launch_bounds__(kThreads, 2) void gemm_pieces(int64_t m_base, int64_t M, int64_t N, int64_t K,
+                                                            const float* __restrict__ A, int64_t lda,
+                                                            const float* __restrict__ B, int64_t ldb,
+                                                            float* __restrict__ C, int64_t ldc, float beta,
+                                                            int epi, int64_t k_per_split,
+                                                            float* __restrict__ partial, int vecA, int vecB) {
+  constexpr int BK = kPieceBK, WN = 2;
+  constexpr int TM = BM / 2 / 32, TN = BN / WN / 32;
+  static_assert(TM >= 1 && TN >= 1, "wave tile must hold at least one 32x32 MFMA tile");
+  using LoadA = typename std::conditional<TA, MContigK4<BM>, KContig<BM, BK>>::type;
+  using LoadB = typename std::conditional<TB, KContig<BN, BK>, MContigK4<BN>>::type;
+
+  __shared__ __attribute__((aligned(16))) uint16_t As[3][BM][kPieceLd];
+  __shared__ __attribute__((aligned(16))) uint16_t Bs[3][BN][kPieceLd];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  int64_t tile_m, tile_n, split;
+  if (!decode_tile(M - m_base, N, K, BM, BN, k_per_split, &tile_m, &tile_n, &split)) return;
+  const int64_t m0 = m_base + tile_m * BM;
+  const int64_t n0 = tile_n * BN;
+  const int64_t kb = split * k_per_split;
+  const int64_t ke = min(K, kb + k_per_split);
+
+  float16v acc[TM][TN], fine[TM][TN];  // products of the two upper pieces; all smaller products
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int64_t col = n0 + (wn * TN + j) * 32 + fcol;
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int64_t row = m0 + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * frow + (r % 4);
-        if (whole || (row < M && col < N)) {
-          float* dst = out + row * ldo + col;
-          if (to_partial) {
-            *dst = acc[i][j][r];
-          } else {
-            const float old = (beta != 0.f || epi == MGGCN_EPI_RELU_MASK) ? *dst : 0.f;
-            *dst = gemm_epilogue(acc[i][j][r], old, beta, epi);
-          }
-        }
-      }
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = fine[i][j][r] = 0.f;
+
+  float ra[LoadA::kRegs], rb[LoadB::kRegs];
+#pragma unroll
+  for (int i = 0; i < LoadA::kRegs; ++i) ra[i] = 0.f;
+#pragma unroll
+  for (int i = 0; i < LoadB::kRegs; ++i) rb[i] = 0.f;
+  const bool whole = kFast && m0 + BM <= M;  // uniform over the block
+  auto load_step = [&](int64_t k) {
+    if (whole && k + BK <= ke) {
+      LoadA::template load<true>(A, lda, m0, M, k, ke, 4, ra);
+      LoadB::template load<true>(B, ldb, n0, N, k, ke, 4, rb);
+    } else {
+      LoadA::template load<false>(A, lda, m0, M, k, ke, vecA, ra);
+      LoadB::template load<false>(B, ldb, n0, N, k, ke, vecB, rb);
     }
+  };
+  load_step(kb);
+
+  const int frow = lane >> 5, fcol = lane & 31;
+  for (int64_t k0 = kb; k0 < ke; k0 += BK) {
+    if constexpr (TA) LoadA::store(As, ra); else store_pieces_kcontig<BM>(As, ra);
+    if constexpr (TB) store_pieces_kcontig<BN>(Bs, rb); else LoadB::store(Bs, rb);
+    __syncthreads();
+    if (k0 + BK < ke) load_step(k0 + BK);  // in flight during the matrix instructions below
+#pragma unroll
+    for (int ks = 0; ks < BK; ks += 16) {
+      bf16x8 a[TM][3], b[TN][3];
+#pragma unroll
+      for (int pl = 0; pl < 3; ++pl) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+          a[i][pl] = *reinterpret_cast<const bf16x8*>(&As[pl][(wm * TM + i) * 32 + fcol][ks + 8 * frow]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          b[j][pl] = *reinterpret_cast<const bf16x8*>(&Bs[pl][(wn * TN + j) * 32 + fcol][ks + 8 * frow]);
+      }
+      // (piece of a, piece of b), smallest products first; consecutive instructions go to
+      // different accumulators.  The five small products have an accumulator of their own: the
+      // matrix unit cuts an addend off below the accumulator's last bits instead of rounding it,
+      // and next to the large sum that bias of the small terms would add up over a long K
+      // (measured on positive operands: -2e-5 relative at K = 16384 in one accumulator, none in two).
+      constexpr int kOrder[5][2] = {{2, 0}, {0, 2}, {1, 1}, {1, 0}, {0, 1}};
+#pragma unroll
+      for (int o = 0; o < 5; ++o)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            fine[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][kOrder[o][0]], b[j][kOrder[o][1]], fine[i][j], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][0], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] += fine[i][j][r];
+  store_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, whole, M, N, split, C, ldc, beta, epi, partial);
 }
 
 // Sum of the split-K partial products, in a fixed order: 8 lanes share one output element, each
@@ -303,27 +533,31 @@ __global__ __launch_bounds__(kThreads) void gemm_reduce_splits(int64_t M, int64_
 }
 
 struct Shape {
-  int bk;
+  bool pieces;  // the bfloat16-piece kernel (128 x bn tiles, k-steps of 32) instead of the fp32 one
+  int bn, bk;
   int64_t tiles_m, tiles_n;
   int splits;
   int64_t k_per_split;
 };
 
-constexpr int kBM = 128, kBN = 64;  // 72 VGPRs + 32 accumulators: 4 wavefronts per SIMD
+constexpr int kBM = 128, kBN = 64;  // fp32 kernel: 72 VGPRs + 32 accumulators, 4 wavefronts per SIMD
 
-Shape plan_shape(int opA, int64_t M, int64_t N, int64_t K) {
+// pieces: the caller asked for the bfloat16-piece kernel (it needs two k-steps of 32 to pay)
+Shape plan_shape(bool pieces, int opA, int64_t M, int64_t N, int64_t K) {
   Shape s;
+  s.pieces = pieces && K >= 64;
   s.bk = (K >= 64) ? 32 : 16;
+  s.bn = s.pieces ? (N > 64 ? 128 : 64) : kBN;
   const int BK = s.bk;
   s.tiles_m = ceil_div(std::max<int64_t>(M, 1), kBM);
-  s.tiles_n = ceil_div(std::max<int64_t>(N, 1), kBN);
+  s.tiles_n = ceil_div(std::max<int64_t>(N, 1), s.bn);
   s.splits = 1;
   s.k_per_split = std::max<int64_t>(align_up((size_t)std::max<int64_t>(K, 1), BK), BK);
   if (opA == MGGCN_OP_T && K > 4096) {
     const int64_t tiles = s.tiles_m * s.tiles_n;
-    // all workgroups resident at once: 256 CUs x 4 (a few more would run as a second round
-    // behind the first and double the kernel's time)
-    int64_t want = std::max<int64_t>(1024 / tiles, 1);
+    // all workgroups resident at once: 256 CUs x 4, or x 2 for the piece kernel with its 60 KB of
+    // LDS (a few more would run as a second round behind the first and double the kernel's time)
+    int64_t want = std::max<int64_t>((s.pieces ? 512 : 1024) / tiles, 1);
     want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
     want = std::max<int64_t>(want, 1);
     s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
@@ -348,52 +582,56 @@ struct GemmArgs {
   hipStream_t st;
 };
 
+#define MGGCN_GEMM_ARGS \
+  0, g.M, g.N, g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, g.beta, g.epi, s.k_per_split, g.partial, g.vecA, g.vecB
+
 template <int BK, bool kFast>
-int launch_rows(const GemmArgs& g, const Shape& s, int64_t m_base, int64_t m_tiles) {
-  if (m_tiles <= 0) return MGGCN_OK;
-  // unsplit: whole groups of 8 M tiles (one per XCD), the kernel drops the padding
-  const int64_t nblk = s.splits == 1 ? kXcds * ceil_div(m_tiles, kXcds) * s.tiles_n
-                                     : (int64_t)s.splits * m_tiles * s.tiles_n;
-  MGGCN_REQUIRE(nblk < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "GeMM grid of %lld x %lld x %d tiles too large",
-                (long long)m_tiles, (long long)s.tiles_n, s.splits);
-  dim3 grid((unsigned)nblk, 1, 1);
-#define MGGCN_GEMM_LAUNCH(TA, TB)                                                                              \
-  gemm_mfma<kBM, kBN, BK, 4, 1, TA, TB, kFast><<<grid, kThreads, 0, g.st>>>(                                   \
-      m_base, g.M, g.N, g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, g.beta, g.epi, s.k_per_split, g.partial, g.vecA, \
-      g.vecB)
+void launch_fp32(const GemmArgs& g, const Shape& s, dim3 grid) {
+#define MGGCN_GEMM_LAUNCH(TA, TB) gemm_mfma<kBM, kBN, BK, 4, 1, TA, TB, kFast><<<grid, kThreads, 0, g.st>>>(MGGCN_GEMM_ARGS)
   if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(false, false);
   else if (g.opA == MGGCN_OP_T && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(true, false);
   else if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_T) MGGCN_GEMM_LAUNCH(false, true);
   else MGGCN_GEMM_LAUNCH(true, true);
 #undef MGGCN_GEMM_LAUNCH
+}
+
+template <int BN, bool kFast>
+void launch_pieces(const GemmArgs& g, const Shape& s, dim3 grid) {
+#define MGGCN_GEMM_LAUNCH(TA, TB) gemm_pieces<kBM, BN, TA, TB, kFast><<<grid, kThreads, 0, g.st>>>(MGGCN_GEMM_ARGS)
+  if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(false, false);
+  else if (g.opA == MGGCN_OP_T && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(true, false);
+  else if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_T) MGGCN_GEMM_LAUNCH(false, true);
+  else MGGCN_GEMM_LAUNCH(true, true);
+#undef MGGCN_GEMM_LAUNCH
+}
+#undef MGGCN_GEMM_ARGS
+
+int launch_all(const GemmArgs& g, const Shape& s) {
+  // unsplit: whole groups of 8 M tiles (one per XCD), the kernel drops the padding
+  const int64_t nblk = s.splits == 1 ? kXcds * ceil_div(s.tiles_m, kXcds) * s.tiles_n
+                                     : (int64_t)s.splits * s.tiles_m * s.tiles_n;
+  MGGCN_REQUIRE(nblk < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "GeMM grid of %lld x %lld x %d tiles too large",
+                (long long)s.tiles_m, (long long)s.tiles_n, s.splits);
+  const dim3 grid((unsigned)nblk, 1, 1);
+  // whole tiles along N and 16-byte rows: interior blocks load without any check
+  const bool fast = g.vecA == 4 && g.vecB == 4 && g.N % s.bn == 0;
+  if (s.pieces) {
+    if (s.bn == 128) fast ? launch_pieces<128, true>(g, s, grid) : launch_pieces<128, false>(g, s, grid);
+    else fast ? launch_pieces<64, true>(g, s, grid) : launch_pieces<64, false>(g, s, grid);
+  } else if (s.bk == 32) {
+    fast ? launch_fp32<32, true>(g, s, grid) : launch_fp32<32, false>(g, s, grid);
+  } else {
+    fast ? launch_fp32<16, true>(g, s, grid) : launch_fp32<16, false>(g, s, grid);
+  }
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
 }
 
-template <int BK>
-int launch_all(const GemmArgs& g, const Shape& s) {
-  const bool fast_ok = g.vecA == 4 && g.vecB == 4 && g.N % kBN == 0;
-  return fast_ok ? launch_rows<BK, true>(g, s, 0, s.tiles_m) : launch_rows<BK, false>(g, s, 0, s.tiles_m);
-}
-
 }  // namespace
-}  // namespace mggcn
 
-using namespace mggcn;
-
-extern "C" {
-
-size_t mggcn_gemm_workspace_bytes(int opA, int opB, int64_t M, int64_t N, int64_t K) {
-  (void)opB;
-  if (M <= 0 || N <= 0 || K <= 0) return 0;
-  const Shape s = plan_shape(opA, M, N, K);
-  if (s.splits <= 1) return 0;
-  return align_up((size_t)s.splits * (size_t)M * (size_t)N * sizeof(float), kWsAlign);
-}
-
-int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
-               const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
-               size_t ws_bytes, void* stream) {
+int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+             const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
+             size_t ws_bytes, void* stream) {
   MGGCN_REQUIRE((opA == MGGCN_OP_N || opA == MGGCN_OP_T) && (opB == MGGCN_OP_N || opB == MGGCN_OP_T),
                 MGGCN_E_INVALID_ARG, "unknown op (%d, %d)", opA, opB);
   MGGCN_REQUIRE(M >= 0 && N >= 0 && K >= 0, MGGCN_E_INVALID_ARG, "negative size M=%lld N=%lld K=%lld",
@@ -411,10 +649,10 @@ int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A
   if (M == 0 || N == 0) return MGGCN_OK;
   MGGCN_REQUIRE(C != nullptr, MGGCN_E_INVALID_ARG, "C is NULL");
   MGGCN_REQUIRE(K == 0 || (A && B), MGGCN_E_INVALID_ARG, "A / B is NULL");
-  const Shape s = plan_shape(opA, M, N, std::max<int64_t>(K, 1));
+  const Shape s = plan_shape(pieces, opA, M, N, std::max<int64_t>(K, 1));
   float* partial = nullptr;
   if (s.splits > 1) {
-    const size_t need = mggcn_gemm_workspace_bytes(opA, opB, M, N, K);
+    const size_t need = mggcn_gemm_workspace_bytes(opA, opB, M, N, K);  // one size for both kernels
     MGGCN_REQUIRE(ws && aligned(ws, kWsAlign), MGGCN_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
     MGGCN_REQUIRE(ws_bytes >= need, MGGCN_E_WORKSPACE, "workspace too small: %zu bytes given, %zu needed",
                   ws_bytes, need);
@@ -428,7 +666,7 @@ int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A
   GemmArgs g{opA, opB, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial, vec_width(A, lda), vec_width(B, ldb),
              as_stream(stream)};
   hipStream_t st = g.st;
-  const int rc = (s.bk == 32) ? launch_all<32>(g, s) : launch_all<16>(g, s);
+  const int rc = launch_all(g, s);
   if (rc) return rc;
   if (partial) {
     gemm_reduce_splits<<<(unsigned)ceil_div(M * N * 8, kThreads), kThreads, 0, st>>>(M, N, s.splits, partial,
@@ -436,6 +674,33 @@ int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A
     MGGCN_LAUNCH_CHECK();
   }
   return MGGCN_OK;
+}
+
+}  // namespace mggcn
+
+using namespace mggcn;
+
+extern "C" {
+
+size_t mggcn_gemm_workspace_bytes(int opA, int opB, int64_t M, int64_t N, int64_t K) {
+  (void)opB;
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  // enough for either kernel: they cut the inner dimension into different numbers of parts
+  const int splits = std::max(plan_shape(false, opA, M, N, K).splits, plan_shape(true, opA, M, N, K).splits);
+  if (splits <= 1) return 0;
+  return align_up((size_t)splits * (size_t)M * (size_t)N * sizeof(float), kWsAlign);
+}
+
+int mggcn_gemm(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+               const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
+               size_t ws_bytes, void* stream) {
+  return gemm_run(false, opA, opB, M, N, K, A, lda, B, ldb, beta, epilogue, C, ldc, ws, ws_bytes, stream);
+}
+
+int mggcn_gemm_bf16x3(int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,
+                      const float* B, int64_t ldb, float beta, int epilogue, float* C, int64_t ldc, void* ws,
+                      size_t ws_bytes, void* stream) {
+  return gemm_run(true, opA, opB, M, N, K, A, lda, B, ldb, beta, epilogue, C, ldc, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

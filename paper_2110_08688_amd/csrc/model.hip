@@ -31,6 +31,7 @@ struct mggcn_model {
   bool gather_bf16 = false;  // every SpMM gathers a bfloat16 copy of its operand
   size_t off_bf16 = 0;       // that copy: n x padded_ld(widest SpMM) 2-byte elements
   int32_t bf16_width = 0;    // the widest SpMM operand it was sized for
+  bool gemm_pieces = false;  // MGGCN_MODEL_GEMM_BF16X3
 };
 
 namespace mggcn {
@@ -86,7 +87,7 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
   *out = nullptr;
   MGGCN_REQUIRE(g != nullptr && dims != nullptr, MGGCN_E_INVALID_ARG, "graph / dims is NULL");
   MGGCN_REQUIRE(L >= 1 && L <= 64, MGGCN_E_INVALID_ARG, "layer count %d outside [1, 64]", L);
-  MGGCN_REQUIRE((flags & ~(MGGCN_MODEL_CACHE_INPUT | MGGCN_MODEL_GATHER_BF16)) == 0, MGGCN_E_INVALID_ARG,
+  MGGCN_REQUIRE((flags & ~(MGGCN_MODEL_CACHE_INPUT | MGGCN_MODEL_GATHER_BF16 | MGGCN_MODEL_GEMM_BF16X3)) == 0, MGGCN_E_INVALID_ARG,
                 "unknown model flags 0x%x", flags);
   MGGCN_REQUIRE(g->fwd.n_rows == g->fwd.n_cols, MGGCN_E_INVALID_ARG,
                 "a model needs a square graph, got %d x %d", g->fwd.n_rows, g->fwd.n_cols);
@@ -104,6 +105,8 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
     m->L = L;
     m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
     m->gather_bf16 = (flags & MGGCN_MODEL_GATHER_BF16) != 0;
+    m->gemm_pieces = (flags & MGGCN_MODEL_GEMM_BF16X3) != 0;
+    m->gemm_pieces = (flags & MGGCN_MODEL_GEMM_BF16X3) != 0;
     m->dims.assign(dims, dims + L + 1);
     m->orders.resize(L);
     m->ld_act.resize(L);
@@ -222,7 +225,7 @@ int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   if (m->orders[l] == MGGCN_ORDER_GEMM_FIRST) {
     // Eq. 5 then Eq. 6-7:  HW = H W ;  H' = relu(A^ HW)
     const int64_t ldt = padded_ld(d_out);
-    rc = mggcn_gemm(MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, H_in, ld_in, W, ldw, 0.f, MGGCN_EPI_NONE, tmp,
+    rc = gemm_run(m->gemm_pieces, MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, H_in, ld_in, W, ldw, 0.f, MGGCN_EPI_NONE, tmp,
                     ldt, nullptr, 0, stream);
     if (rc) return rc;
     return gathered_spmm(m, MGGCN_OP_N, tmp, ldt, d_out, epi, H_out, ld_out, stream);
@@ -233,7 +236,7 @@ int mggcn_layer_fwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
     rc = gathered_spmm(m, MGGCN_OP_N, H_in, ld_in, d_in, MGGCN_EPI_NONE, P, m->ld_p[l], stream);
     if (rc) return rc;
   }
-  return mggcn_gemm(MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, P, m->ld_p[l], W, ldw, 0.f, epi, H_out, ld_out,
+  return gemm_run(m->gemm_pieces, MGGCN_OP_N, MGGCN_OP_N, m->n, d_out, d_in, P, m->ld_p[l], W, ldw, 0.f, epi, H_out, ld_out,
                     nullptr, 0, stream);
 }
 
@@ -265,19 +268,19 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
     const int64_t ldt = padded_ld(d_out);
     rc = gathered_spmm(m, MGGCN_OP_T, G, ldg, d_out, MGGCN_EPI_NONE, tmp, ldt, stream);
     if (rc) return rc;
-    rc = mggcn_gemm(MGGCN_OP_T, MGGCN_OP_N, d_in, d_out, m->n, H_in, ld_in, tmp, ldt, 0.f, MGGCN_EPI_NONE, W_G,
+    rc = gemm_run(m->gemm_pieces, MGGCN_OP_T, MGGCN_OP_N, d_in, d_out, m->n, H_in, ld_in, tmp, ldt, 0.f, MGGCN_EPI_NONE, W_G,
                     ldwg, gws, m->gemm_ws_bytes, stream);
     if (rc || !H_G) return rc;
-    return mggcn_gemm(MGGCN_OP_N, MGGCN_OP_T, m->n, d_in, d_out, tmp, ldt, W, ldw, 0.f, hg_epi, H_G, ldhg,
+    return gemm_run(m->gemm_pieces, MGGCN_OP_N, MGGCN_OP_T, m->n, d_in, d_out, tmp, ldt, W, ldw, 0.f, hg_epi, H_G, ldhg,
                       nullptr, 0, stream);
   }
   // SpMM-first association:  W_G = (A^ H)^T Z_G ;  U = Z_G W^T ;  H_G = A^^T U
   const float* P = reinterpret_cast<const float*>(m->arena + m->off_p[l]);
-  rc = mggcn_gemm(MGGCN_OP_T, MGGCN_OP_N, d_in, d_out, m->n, P, m->ld_p[l], G, ldg, 0.f, MGGCN_EPI_NONE, W_G,
+  rc = gemm_run(m->gemm_pieces, MGGCN_OP_T, MGGCN_OP_N, d_in, d_out, m->n, P, m->ld_p[l], G, ldg, 0.f, MGGCN_EPI_NONE, W_G,
                   ldwg, gws, m->gemm_ws_bytes, stream);
   if (rc || !H_G) return rc;
   const int64_t ldu = padded_ld(d_in);
-  rc = mggcn_gemm(MGGCN_OP_N, MGGCN_OP_T, m->n, d_in, d_out, G, ldg, W, ldw, 0.f, MGGCN_EPI_NONE, tmp, ldu,
+  rc = gemm_run(m->gemm_pieces, MGGCN_OP_N, MGGCN_OP_T, m->n, d_in, d_out, G, ldg, W, ldw, 0.f, MGGCN_EPI_NONE, tmp, ldu,
                   nullptr, 0, stream);
   if (rc) return rc;
   return gathered_spmm(m, MGGCN_OP_T, tmp, ldu, d_in, hg_epi, H_G, ldhg, stream);
