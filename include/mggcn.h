@@ -118,7 +118,9 @@ int mggcn_csr_normalize64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_
 /* Explicit transpose of a CSR matrix (the paper keeps A^ and A^^T both, for the backward
  * SpMM of Eq. 9).  Rows of the result have ascending columns; the result is unique, so it
  * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries.  32-bit row offsets only
- * (fewer than 2^31 entries). */
+ * (fewer than 2^31 entries).  The input must be a well-formed CSR (what mggcn_csr_normalize
+ * writes): nothing is validated here; a column index outside [0, n_cols) is never followed, but
+ * the result is then meaningless. */
 size_t mggcn_csr_transpose_workspace_bytes(int32_t n_rows, int32_t n_cols, int64_t nnz);
 
 int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr,
@@ -133,7 +135,11 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * crosses the column-panel boundaries (a few bytes per row, written to pinned host memory it
  * allocates and frees itself), SYNCHRONISES the stream, and builds the segment tables on the host.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the
  * case for the symmetric normalisation of an undirected graph); op T then runs on A^ itself.
- * The CSR arrays are borrowed, not copied: they must outlive the handle.
+ * The CSR arrays are borrowed, not copied: they must outlive the handle.  _create checks that
+ * rowptr starts at 0 and never decreases and that every column index lies in [0, n_cols)
+ * (MGGCN_E_BAD_CSR otherwise, so that no product ever gathers outside X); ascending columns
+ * inside a row, which the panel forms rely on, are the caller's to guarantee
+ * (mggcn_csr_normalize writes them so).
  * seg_len = maximum entries per segment (0 = library default).
  * n_panels = number of column panels the SpMM walks one after the other so that all wavefronts
  * in flight gather from the same slice of X (0 = automatic: forms for 2, 4, 8, ... panels are

@@ -63,6 +63,14 @@ __global__ __launch_bounds__(kSpmmThreads) void panel_cuts(int32_t n_rows, int32
   cuts[idx] = (uint32_t)lo;
 }
 
+// A column index outside [0, n_cols) would send a gather outside X: found here, once, instead.
+__global__ __launch_bounds__(kSpmmThreads) void check_columns(int64_t nnz, int32_t n_cols,
+                                                               const int32_t* __restrict__ colidx,
+                                                               uint32_t* __restrict__ bad) {
+  const int64_t k = (int64_t)blockIdx.x * kSpmmThreads + threadIdx.x;
+  if (k < nnz && (uint32_t)colidx[k] >= (uint32_t)n_cols) *bad = 1u;  // every writer stores the same value
+}
+
 // Row-segment tables for `n_panels` column panels, in two passes over the rows: count the tasks
 // of every (panel, length), turn the counts into the positions of a longest-first counting sort,
 // then write every task to its final place (row order is kept inside a length).
@@ -369,6 +377,20 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
     MGGCN_REQUIRE(o->nnz < ((int64_t)1 << 32), MGGCN_E_OVERFLOW,
                   "%lld entries: entry offsets are held in 32 unsigned bits", (long long)o->nnz);
     MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
+    struct Pinned {  // freed on every way out, a failed allocation of the tables included
+      uint32_t* p = nullptr;
+      ~Pinned() { if (p) (void)hipHostFree(p); }
+    };
+    if (o->nnz > 0) {
+      Pinned bad;
+      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&bad.p), sizeof(uint32_t), hipHostMallocDefault));
+      *bad.p = 0u;
+      check_columns<<<(unsigned)ceil_div(o->nnz, kThreads), kThreads, 0, s>>>(o->nnz, nc, ci, bad.p);
+      hipError_t e = hipGetLastError();
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      if (e != hipSuccess) return fail(MGGCN_E_HIP, "column index check failed: %s", hipGetErrorString(e));
+      MGGCN_REQUIRE(*bad.p == 0u, MGGCN_E_BAD_CSR, "a column index lies outside [0, %d)", nc);
+    }
     build_task_set(&o->flat, nr, h, nullptr, 0, 0, 1, seg_len);
     const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
     if (Pmax > 1 && nr > 0) {
@@ -377,10 +399,7 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
       // (an automatic set has power-of-two panel counts over one common finest width).
       const int32_t n_cuts = Pmax - 1;
       const int64_t width = ceil_div(std::max(nc, 1), Pmax);
-      struct Pinned {  // freed on every way out, a failed allocation of the tables included
-        uint32_t* p = nullptr;
-        ~Pinned() { if (p) (void)hipHostFree(p); }
-      } pinned;
+      Pinned pinned;
       MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&pinned.p), sizeof(uint32_t) * (size_t)nr * (size_t)n_cuts, hipHostMallocDefault));
       uint32_t* cuts = pinned.p;
       const int64_t items = (int64_t)nr * n_cuts;

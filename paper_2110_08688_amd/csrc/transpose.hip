@@ -25,11 +25,12 @@ __global__ __launch_bounds__(kThreads) void zero_counts(int64_t n, int32_t* out)
   if (k < n) out[k] = 0;
 }
 
-__global__ __launch_bounds__(kThreads) void count_columns(int64_t nnz,
+// integer histogram; an index outside [0, n_cols) (malformed input) is left out rather than followed
+__global__ __launch_bounds__(kThreads) void count_columns(int64_t nnz, int32_t n_cols,
                                                            const int32_t* __restrict__ colidx,
                                                            int32_t* __restrict__ counts) {
   const int64_t k = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-  if (k < nnz) atomicAdd(&counts[colidx[k]], 1);  // integer histogram
+  if (k < nnz && (uint32_t)colidx[k] < (uint32_t)n_cols) atomicAdd(&counts[colidx[k]], 1);
 }
 
 // pos[p] = original position of the p-th entry in column-major order
@@ -122,7 +123,7 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
   MGGCN_LAUNCH_CHECK();
   if (nnz > 0) {
     const unsigned nb = (unsigned)ceil_div(nnz, kThreads);
-    count_columns<<<nb, kThreads, 0, s>>>(nnz, colidx, w.counts);
+    count_columns<<<nb, kThreads, 0, s>>>(nnz, n_cols, colidx, w.counts);
     MGGCN_LAUNCH_CHECK();
     iota_i32<<<nb, kThreads, 0, s>>>(nnz, w.pos_in);
     MGGCN_LAUNCH_CHECK();

@@ -143,6 +143,29 @@ def test_csr_normalize_rejects_malformed(mg, dev):
         assert ei.value.code == mg.binding.E_BAD_CSR
 
 
+def test_graph_create_rejects_malformed(mg, dev):
+    """a handle is only made of offsets that start at 0 and never decrease and of column indices
+    inside the matrix: no product can then gather outside its operand"""
+    ones = to_dev(np.ones(3, np.float32), dev)
+    good_rp = to_dev(np.array([0, 2, 3], np.int32), dev)
+    cases = [([0, 2, 3], [0, 2, 1]),    # column 2 of a 2 x 2 matrix
+             ([0, 2, 3], [0, -1, 1]),   # negative column
+             ([1, 2, 3], [0, 1, 1]),    # offsets do not start at 0
+             ([0, 3, 2], [0, 1, 1])]    # offsets decrease
+    for rp, ci in cases:
+        with pytest.raises(mg.MggcnError) as ei:
+            mg.Graph(2, 2, to_dev(np.array(rp, np.int32), dev), to_dev(np.array(ci, np.int32), dev), ones, F_max=8)
+        assert ei.value.code == mg.binding.E_BAD_CSR, (rp, ci)
+    # the transposed operator is checked as well
+    with pytest.raises(mg.MggcnError) as ei:
+        mg.Graph(2, 2, good_rp, to_dev(np.array([0, 1, 1], np.int32), dev), ones,
+                 transpose=(good_rp, to_dev(np.array([0, 1, 7], np.int32), dev), ones), F_max=8)
+    assert ei.value.code == mg.binding.E_BAD_CSR
+    G = mg.Graph(2, 2, good_rp, to_dev(np.array([0, 1, 1], np.int32), dev), ones, F_max=8)
+    Y = mg.mggcn_spmm(G, mg.OP_N, to_dev(np.array([[1.0], [10.0]], np.float32), dev))
+    assert np.array_equal(Y.cpu().numpy(), np.array([[11.0], [10.0]], np.float32))
+
+
 @pytest.mark.parametrize("shape", [(30, 45, 0.15), (1000, 700, 0.02), (64, 64, 0.0)])
 def test_csr_transpose_exact(mg, dev, ref, shape):
     n, m, dens = shape
