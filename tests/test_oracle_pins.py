@@ -670,3 +670,52 @@ def test_epoch_bf16_recorded_and_injected_operands(ref):
     bumped[0][3, 2] += 1
     loss4, _, _, _ = ref.epoch_bf16(n, rp, ci, val, X, labels, Ws, orders=orders, fwd_codes=bumped)
     assert loss4 != loss and abs(loss4 - loss) < 1e-3
+
+
+# ----------------------------------------------------------------------------------------------
+# the arithmetic behind the GeMM extension on the bfloat16 matrix instructions: facts about fp32
+# numbers, checked here in numpy, that the tolerance of its GPU tests rests on (no product code)
+# ----------------------------------------------------------------------------------------------
+
+def _three_pieces(x):
+    """x (fp32) -> its upper 16 bits, the upper 16 bits of what that leaves, and the rest"""
+    top = (x.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+    r1 = x - top
+    mid = (r1.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+    low = r1 - mid
+    return top, mid, low
+
+
+def test_fp32_is_the_exact_sum_of_three_bfloat16_pieces():
+    rng = np.random.default_rng(12)
+    bits = rng.integers(0, 2 ** 32, size=2_000_000, dtype=np.uint64).astype(np.uint32)
+    x = bits.view(np.float32)
+    x = x[np.isfinite(x) & (np.abs(x) > 2.0 ** -100) & (np.abs(x) < 2.0 ** 100)]
+    x = np.concatenate([x, np.float32([1.0, -1.0, 1.0 + 2.0 ** -23, 2.0 - 2.0 ** -23, 3.0, 0.1, 1e-30, -7e29, 0.0])])
+    top, mid, low = _three_pieces(x)
+    with np.errstate(over="ignore"):
+        # every piece is a bfloat16 number (its lower 16 bits are zero) ...
+        for piece in (top, mid, low):
+            assert np.all((piece.view(np.uint32) & np.uint32(0xFFFF)) == 0)
+        # ... the three add up to x exactly, and both subtractions were exact in fp32
+        assert np.array_equal(top.astype(np.float64) + mid.astype(np.float64) + low.astype(np.float64), x.astype(np.float64))
+        assert np.array_equal((x.astype(np.float64) - top.astype(np.float64)).astype(np.float32).astype(np.float64),
+                              x.astype(np.float64) - top.astype(np.float64))
+    ax = np.abs(x.astype(np.float64))
+    assert np.all(np.abs(mid) <= 2.0 ** -7 * ax) and np.all(np.abs(low) <= 2.0 ** -15 * ax)
+
+
+def test_six_of_nine_piece_products_lose_less_than_2_to_minus_21():
+    rng = np.random.default_rng(13)
+    a = rng.standard_normal(1_000_000).astype(np.float32)
+    b = (rng.standard_normal(1_000_000) * 37.0).astype(np.float32)
+    a0, a1, a2 = (p.astype(np.float64) for p in _three_pieces(a))
+    b0, b1, b2 = (p.astype(np.float64) for p in _three_pieces(b))
+    kept = a2 * b0 + a0 * b2 + a1 * b1 + a1 * b0 + a0 * b1 + a0 * b0   # each term exact: 8 x 8 significand bits
+    exact = a.astype(np.float64) * b.astype(np.float64)
+    lost = np.abs(exact - kept)
+    assert np.all(lost <= 2.0 ** -21 * np.abs(exact))
+    assert lost.mean() <= 2.0 ** -23 * np.abs(exact).mean()  # on average a fraction of one fp32 rounding
+    # a product of two pieces has at most 16 significand bits: exact in the fp32 the matrix unit adds in
+    p = (a1 * b1)
+    assert np.array_equal(p.astype(np.float32).astype(np.float64), p)
