@@ -155,3 +155,51 @@ def test_epoch_with_gemm_bf16x3(mg, dev, ref, cfg_name, dims, flags):
         a = WG[l].cpu().numpy()
         assert np.array_equal(a, WG2[l].cpu().numpy()), "epoch must be reproducible bit for bit"
         assert_rows_close(a, rWG[l], what=f"W_G[{l}]")
+
+
+def test_gemm_random_cases_both_entry_points(mg, dev, ref):
+    """Seeded random shapes, op combinations, leading dimensions and base-pointer offsets (4-, 8- and
+    16-byte aligned operands take different loaders), β and epilogues, through mggcn_gemm and
+    mggcn_gemm_bf16x3 alike."""
+    import torch
+
+    rng = np.random.default_rng(2024)
+
+    def view(a, ld, off):
+        r, c = a.shape
+        buf = torch.zeros(off + max(r, 1) * ld + 8, dtype=torch.float32, device=dev)
+        v = buf[off: off + r * ld].view(r, ld)[:, :c]
+        v.copy_(to_dev(a, dev))
+        return v
+
+    for case in range(48):
+        M = int(rng.choice([1, 5, 63, 64, 127, 128, 129, 300, 1000]))
+        N = int(rng.choice([1, 7, 16, 41, 47, 64, 65, 100, 128, 130, 256]))
+        K = int(rng.choice([1, 15, 16, 63, 64, 65, 96, 100, 128, 257, 602, 5000]))
+        opA, opB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        A = wl.normal_f32(case, 61, (M, K))
+        Bm = wl.normal_f32(case, 62, (K, N))
+        a = A if opA == 0 else np.ascontiguousarray(A.T)
+        b = Bm if opB == 0 else np.ascontiguousarray(Bm.T)
+        lda = a.shape[1] + int(rng.choice([0, 1, 2, 3, 4, 6]))
+        ldb = b.shape[1] + int(rng.choice([0, 1, 2, 4]))
+        ldc = N + int(rng.choice([0, 1, 3]))
+        offs = [int(rng.choice([0, 1, 2, 4])) for _ in range(3)]
+        beta = float(rng.integers(0, 2))
+        epi = int(rng.choice([mg.EPI_NONE, mg.EPI_RELU, mg.EPI_RELU_MASK])) if beta == 0 else int(rng.choice([mg.EPI_NONE, mg.EPI_RELU]))
+        C0 = wl.normal_f32(case, 63, (M, N))
+        want = ref.gemm(ref.OP_N, ref.OP_N, A.astype(np.float64), Bm.astype(np.float64))
+        if beta:
+            want = want + C0
+        if epi == mg.EPI_RELU:
+            want = np.maximum(want, 0)
+        if epi == mg.EPI_RELU_MASK:
+            want = np.where(C0 > 0, want, 0)
+        for name, fn in (("fp32", mg.mggcn_gemm), ("bf16x3", mg.mggcn_gemm_bf16x3)):
+            say(f"[gemm random {case} {name}] {M}x{N}x{K} op=({opA},{opB}) ld=({lda},{ldb},{ldc}) off={offs} beta={beta} epi={epi}")
+            Cd = view(C0, ldc, offs[2])
+            fn(opA, opB, view(a, lda, offs[0]), view(b, ldb, offs[1]), beta=beta, epilogue=epi, Cm=Cd)
+            got = Cd.cpu().numpy().astype(np.float64)
+            # forward error bound of a dot product: a small multiple of the unit roundoff times |A||B|
+            bound = 2e-5 * (np.abs(A).astype(np.float64) @ np.abs(Bm).astype(np.float64) + beta * np.abs(C0)) + 1e-30
+            assert np.all(np.abs(got - want) <= bound), (name, case, float(np.abs(got - want).max()))
