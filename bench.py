@@ -29,7 +29,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # HBM bytes per launch of the dominant SpMM kernel measured with rocprofv3 --pmc (FETCH_SIZE,
 # WRITE_SIZE, calibrated against a copy of known size); configurations not listed: not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "medium": 2_923_504_002,    # F=128, per panel launch; profiles/spmm_medium_F128_pmc.md
+    "medium": 1_063_667_504,    # F=128, per panel launch; profiles/spmm_medium_F128_pmc.md
     "large": 129_270_000_000,   # F=256, one launch per call; profiles/spmm_large_pmc.md
 }
 

@@ -144,7 +144,8 @@ int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32
  * n_panels = number of column panels the SpMM walks one after the other so that all wavefronts
  * in flight gather from the same slice of X (0 = automatic: forms for 2, 4, 8, ... panels are
  * built as far as the average row length affords, and each product picks the count that brings
- * one panel of its gathered operand down to about 16 MiB, or none for a small operand;
+ * one panel of its gathered operand down to about 12 MiB (16 MiB for a bfloat16 operand), or
+ * none for a small operand;
  * 1 = never; > 1 = always that many).
  * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
  * also holds the partial sums of rows that were cut, for feature widths up to F_max.

@@ -160,10 +160,10 @@ int pow2_floor(int64_t x) {
 
 // Most column panels a matrix affords: every panel costs one more read-modify-write of the output,
 // which an average row of ~50 entries does not earn back even with 2 panels, while ~490 entries
-// carry 8 (measured).
+// carry 16 (measured).
 int32_t max_panels(int32_t n_rows, int64_t nnz) {
   if (n_rows <= 0 || nnz <= 0) return 1;
-  return (int32_t)std::min<int64_t>(pow2_floor(std::max<int64_t>(1, nnz / n_rows / 32)), 32);
+  return (int32_t)std::min<int64_t>(pow2_floor(std::max<int64_t>(1, nnz / n_rows / 30)), 32);
 }
 
 int pow2_ceil(int x) {
@@ -174,14 +174,21 @@ int pow2_ceil(int x) {
 
 // Panel form for a product whose gathered operand has n_cols rows of F elements of elem_bytes:
 // the smallest power-of-two panel count that brings one panel of the operand down to
-// g->panel_bytes (about 16 MiB measured best on MI355X for both 4- and 2-byte elements: a panel
-// that all wavefronts in flight share then lives in L2 / Infinity Cache), among the forms built.
+// the target size (a panel that all wavefronts in flight share then lives in L2 / Infinity
+// Cache), among the forms built.
+// Target size of one panel of the gathered operand.  Measured best on MI355X: about 16 MiB for
+// 2-byte elements and 12 MiB for 4-byte ones -- the read-modify-write of the fp32 output that every
+// panel costs weighs twice as much against a gather of half the bytes.
+int64_t panel_target(const mggcn_graph* g, int elem_bytes) {
+  return std::max<int64_t>(elem_bytes >= 4 ? g->panel_bytes / 4 * 3 : g->panel_bytes, 1);
+}
+
 const TaskSet* pick_panels(const mggcn_graph* g, const Orientation& o, int32_t F, int elem_bytes, int epilogue) {
   // the in-place ReLU' mask needs the old Y at every write, which only the single-panel form provides
   if (o.panelled.empty() || epilogue == MGGCN_EPI_RELU_MASK) return &o.flat;
   if (g->panels_fixed) return &o.panelled.front();
   const int64_t bytes = (int64_t)o.n_cols * F * elem_bytes;
-  const int want = pow2_ceil((int)std::min<int64_t>(ceil_div(bytes, std::max<int64_t>(g->panel_bytes, 1)), 1 << 20));
+  const int want = pow2_ceil((int)std::min<int64_t>(ceil_div(bytes, panel_target(g, elem_bytes)), 1 << 20));
   if (want <= 1) return &o.flat;
   const TaskSet* best = &o.panelled.front();
   for (const TaskSet& ts : o.panelled)
@@ -524,7 +531,7 @@ const TaskSet& plan_passes(const mggcn_graph* g, const Orientation& o, int32_t F
   const TaskSet& ts = *pick_panels(g, o, F, elem_bytes, epilogue);
   int64_t slice = std::max(F, 1);
   if (!g->panels_fixed && ts.n_panels > 1) {
-    const int64_t passes = ceil_div((int64_t)o.n_cols * F * elem_bytes, std::max<int64_t>(g->panel_bytes, 1));
+    const int64_t passes = ceil_div((int64_t)o.n_cols * F * elem_bytes, panel_target(g, elem_bytes));
     if (passes > ts.n_panels) {
       // slices of whole 64-element groups keep every alignment of the full operand; a slice narrower
       // than 512 bytes of a row gathers too little per entry to pay for re-reading the entries
