@@ -330,7 +330,7 @@ def main() -> int:
         ops[f"spmm_fwd_l{l}_F{F}"] = timed(lambda: mg.mggcn_spmm(graph, mg.OP_N, src[:, :F], epilogue=epi, Y=dst[:, :F]), reps)
         if l > 0 or order == mg.ORDER_GEMM_FIRST:
             ops[f"spmm_bwd_l{l}_F{F}"] = timed(lambda: mg.mggcn_spmm(graph, mg.OP_T, src[:, :F], Y=dst[:, :F]), reps)
-        srcb = torch.empty((n, ld), dtype=torch.int16, device=dev)
+        srcb = torch.empty((n, 16 if F <= 16 else (F + 31) // 32 * 32), dtype=torch.int16, device=dev)  # rows on 64-byte multiples, as in the model
         bf16_ops[f"f32_to_bf16_F{F}"] = timed(lambda: mg.mggcn_f32_to_bf16(src[:, :F], dst=srcb[:, :F]), reps)
         bf16_ops[f"spmm_bf16_fwd_l{l}_F{F}"] = timed(
             lambda: mg.mggcn_spmm_bf16(graph, mg.OP_N, srcb[:, :F], epilogue=epi, Y=dst[:, :F]), reps)
