@@ -422,9 +422,9 @@ def test_spmm_automatic_panels_and_feature_slices(mg, dev, ref, monkeypatch, F):
     monkeypatch.setenv("MGGCN_PANEL_MB", "1")
     G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=F)
     monkeypatch.delenv("MGGCN_PANEL_MB")
-    # the fp32 target is 3/4 of the setting; 200 entries per row afford 4 panels; 7 MiB at F=602
-    # then also takes 3 feature slices
-    assert G.panels(602) == 12 and G.panels(100) == 2 and G.panels(16) == 1
+    # the fp32 target is 3/4 of the setting, feature slices are cut for 2/3 of that; 200 entries per
+    # row afford 4 panels; 7 MiB at F=602 then also takes 4 feature slices
+    assert G.panels(602) == 16 and G.panels(100) == 2 and G.panels(16) == 1
     X = wl.normal_f32(55 + F, 6, (n, F))
     Y0 = wl.normal_f32(55 + F, 7, (n, F))
     want = ref.spmm(ref.OP_N, n, n, rp, ci, val.astype(np.float64), X.astype(np.float64))
