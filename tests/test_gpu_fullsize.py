@@ -86,17 +86,20 @@ def test_medium_spmm_all_rows(medium, ref, F, ld, relu):
     assert torch.equal(Yd, Yt)
 
 
-def test_medium_epoch(medium, ref):
+@pytest.mark.parametrize("gemm", ["fp32", "bf16x3"])
+def test_medium_epoch(medium, ref, gemm):
+    """the benchmarked epoch against the oracle's, with the GeMMs on the fp32 matrix instruction and
+    (the extension) on the bfloat16 ones: same oracle, same bounds"""
     import torch
 
     m = medium
     mg, dev, n, cfg = m["mg"], m["dev"], m["n"], m["cfg"]
     X, Ws, labels = cfg.features(n), cfg.weights(), cfg.labels(n)
-    model = mg.Model(m["graph"], cfg.dims)
+    model = mg.Model(m["graph"], cfg.dims, flags=mg.MODEL_GEMM_BF16X3 if gemm == "bf16x3" else 0)
     Xd, Wd = torch.from_numpy(X).to(dev), [torch.from_numpy(w).to(dev) for w in Ws]
     loss, WG = mg.mggcn_epoch(model, Xd, torch.from_numpy(labels).to(dev), Wd)
     torch.cuda.synchronize()
-    say(f"[medium epoch] gpu loss {loss.item():.7f}; running the fp64 oracle epoch on the host ...")
+    say(f"[medium epoch, GeMM {gemm}] gpu loss {loss.item():.7f}; running the fp64 oracle epoch on the host ...")
     # the device's own ReLU' decisions (same forward call, same bits as inside the epoch): a
     # hidden activation that is zero to within rounding is "on" or "off" by a coin toss, and one
     # such entry moves a whole column of W_G[0] by ~1/sqrt(n) of its size
