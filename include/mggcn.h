@@ -16,8 +16,12 @@
  *     enqueued asynchronously and in order on that stream; unless stated otherwise an
  *     entry point does not synchronise, and outputs are valid once the stream has drained.
  *   - Dense matrices are row-major fp32 with an explicit leading dimension in elements
- *     (ld >= number of columns); only the first `cols` entries of a row are read or
- *     written.  Sparse matrices are CSR with int32 `rowptr` (n_rows+1 entries, rowptr[0]=0),
+ *     (ld >= number of columns); only the first `cols` entries of a row are written.  Reads stay
+ *     inside the first `cols` entries too, with one exception: the gathered operand X of
+ *     mggcn_spmm / mggcn_spmm_bf16 on the 16-byte path (16-byte aligned X, ldx a multiple of 4
+ *     floats / 8 bfloat16) is read in whole 16-byte vectors, i.e. up to min(ldx, cols rounded up
+ *     to 4 floats / 8 bfloat16) entries of every row; what lies beyond `cols` never reaches an
+ *     output, but it must be readable memory (it is, inside ldx) and not part of Y.  Sparse matrices are CSR with int32 `rowptr` (n_rows+1 entries, rowptr[0]=0),
  *     int32 `colidx` ascending and duplicate-free inside a row, fp32 `val`; nnz < 2^31.
  *   - Results do not depend on launch order or timing: no floating-point atomics are used,
  *     so repeated calls on the same inputs give bit-identical outputs.
@@ -48,6 +52,13 @@ typedef enum {
   MGGCN_NORM_SYM_SELFLOOP = 0, /* A^_ij = 1/sqrt(d_i d_j), d = entries per row of A~              */
   MGGCN_NORM_MEAN_IN = 1       /* A^_uv = 1/(entries in column v of A~): Eq. 2 of the paper        */
 } mggcn_norm;
+/* Eq. 2 normalises the columns of A, and the paper's layer (Eq. 1, 6) multiplies by the TRANSPOSE of
+ * that matrix: (A^^T H)_v is the average of H over the in-neighbours of v.  mggcn_spmm's op N and the
+ * forward pass of a model multiply by the matrix the graph handle was created with, so to run the
+ * paper's mean-aggregation layer on a MEAN_IN matrix, create the handle with the transpose as the
+ * matrix and the matrix as its transpose: mggcn_graph_create(.., rowptr_t, colidx_t, val_t, rowptr,
+ * colidx, val, ..) with the arrays mggcn_csr_transpose wrote.  (For the symmetric normalisation of an
+ * undirected graph the two coincide.) */
 
 typedef enum { MGGCN_OP_N = 0, MGGCN_OP_T = 1 } mggcn_op;
 
@@ -162,7 +173,7 @@ int mggcn_graph_create(int32_t n_rows, int32_t n_cols, const int32_t* rowptr /*d
                        mggcn_graph** out);
 /* The same with 64-bit row offsets, for matrices of 2^31 entries and more (fewer than 2^32: the
  * segment tables hold entry offsets in 32 unsigned bits; a single row holds fewer than 2^29).
- * Everything else about the handle is unchanged; the sweep form is not available for it. */
+ * Everything else about the handle is unchanged. */
 int mggcn_graph_create64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr /*dev*/,
                          const int32_t* colidx /*dev*/, const float* val /*dev*/,
                          const int64_t* rowptr_t /*dev or NULL*/, const int32_t* colidx_t,
@@ -171,15 +182,16 @@ int mggcn_graph_create64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr /
 size_t mggcn_graph_workspace_bytes(const mggcn_graph* g, int32_t F_max);
 int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws /*dev*/, size_t ws_bytes, void* stream);
 int mggcn_graph_destroy(mggcn_graph* g);
-/* (Re)build the "sweep" form of the operator and use it for every SpMM on this graph: rows dealt
- * to teams of rows_per_team rows (4, 8 or 16; 0 = default) with equal entry totals, each team's
- * entries stored contiguously in (column panel, row, column) order over n_panels panels
- * (0 = default), so that one launch sweeps all teams through the panels together and writes each
- * row of Y once.  mggcn_graph_create builds it by itself for graphs with long rows and a large
- * dense operand; this call forces it (tests, tuning).  Reads the CSR arrays back to the host,
- * SYNCHRONISES, invalidates the binding: call mggcn_graph_bind afterwards.  Column count must
- * fit 28 bits. */
-int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_team, void* stream);
+/* Tuning knobs of a handle (sweeps and tests; the defaults are what was measured best on MI355X).
+ * They change how later products are launched, never their result beyond summation order, and
+ * leave the binding valid.
+ * panel_mib: size in MiB that one column panel of a product's gathered operand is brought down to
+ *   when the panel count is automatic (n_panels = 0 at creation); 0 = leave as it is (default 16:
+ *   16 MiB for a bfloat16 operand, three quarters of it for an fp32 one).
+ * chunk_lanes: lanes of a wavefront that share one gathered row (a power of two up to 64; fewer
+ *   lanes = narrower feature chunks, dealt to workgroups round-robin); 0 = leave as it is,
+ *   -1 = back to the default (as many as the row needs). */
+int mggcn_graph_tune(mggcn_graph* g, int32_t panel_mib, int32_t chunk_lanes);
 /* Number of passes over the entries a plain (epilogue NONE or RELU) fp32 SpMM of width F with
  * the given op makes on this graph: column panels x feature slices (1 = single pass), or a
  * negative status. */
@@ -289,7 +301,8 @@ typedef struct mggcn_model mggcn_model;
  * once (mggcn_model_cache_input) and kept in the arena; the first layer then runs as
  * relu((A^ X) W) forward and W_G = (A^ X)^T Z_G backward with no SpMM at all in either pass --
  * the exact form of the paper's "saving one SpMM" (section "Order of Computation and Saving one
- * SpMM").  Costs one n x d_0 buffer.
+ * SpMM").  Costs one n x d_0 buffer.  mggcn_layer_bwd(l = 0) of such a model takes H_G = NULL only
+ * (MGGCN_E_INVALID_ARG otherwise): the shared temporary is not sized for the gradient of X.
  * MGGCN_MODEL_GATHER_BF16 (beyond the paper, which is fp32 throughout): every SpMM of the model
  * gathers a bfloat16 copy of its dense operand, made by mggcn_f32_to_bf16 just before the product
  * (see mggcn_spmm_bf16); GeMMs, activations, loss and all accumulation stay fp32.  The backward

@@ -37,6 +37,16 @@ def _stream(stream):
     return B.current_stream() if stream is None else stream
 
 
+def _sync(stream):
+    """Wait for the work enqueued on the stream a call used, before its workspace tensor is dropped
+    (PyTorch's allocator would hand the memory to someone else while kernels still use it)."""
+    torch = _torch()
+    if stream is None:
+        torch.cuda.current_stream().synchronize()
+    else:
+        torch.cuda.ExternalStream(int(stream)).synchronize()
+
+
 def mggcn_version() -> int:
     return B.lib().mggcn_version()
 
@@ -67,7 +77,7 @@ def mggcn_csr_normalize(n_rows, n_cols, rowptr_in, colidx_in, mode=NORM_SYM_SELF
     B.check(fill_fn(n_rows, n_cols, B.ptr(rowptr_in), B.ptr(colidx_in), mode, B.ptr(deg_row),
                                   B.ptr(deg_col), B.ptr(rowptr), B.ptr(colidx), B.ptr(val), _ws_ptr(ws),
                                   nbytes, st))
-    torch.cuda.current_stream().synchronize() if stream is None else None  # ws may be freed now
+    _sync(stream)  # ws may be freed now
     return rowptr, colidx, val
 
 
@@ -83,7 +93,7 @@ def mggcn_csr_transpose(n_rows, n_cols, rowptr, colidx, val, stream=None):
     val_t = torch.empty(nnz, dtype=torch.float32, device=dev)
     B.check(L.mggcn_csr_transpose(n_rows, n_cols, nnz, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rowptr_t),
                                   B.ptr(colidx_t), B.ptr(val_t), _ws_ptr(ws), nbytes, _stream(stream)))
-    torch.cuda.current_stream().synchronize() if stream is None else None
+    _sync(stream)
     return rowptr_t, colidx_t, val_t
 
 
@@ -95,7 +105,7 @@ class Graph:
     """Owns an mggcn_graph handle, keeps the CSR tensors and the bound workspace alive."""
 
     def __init__(self, n_rows, n_cols, rowptr, colidx, val, transpose=None, F_max=256, seg_len=0, n_panels=0,
-                 sweep=None, stream=None):
+                 panel_mib=0, chunk_lanes=0, stream=None):
         L = B.lib()
         self.n_rows, self.n_cols = n_rows, n_cols
         self._keep = [rowptr, colidx, val, transpose]
@@ -109,8 +119,8 @@ class Graph:
         self.device = rowptr.device
         self.ws = None
         self.F_max = 0
-        if sweep is not None:  # (n_panels, rows_per_team): force the sweep form
-            B.check(L.mggcn_graph_build_sweep(h, int(sweep[0]), int(sweep[1]), _stream(stream)))
+        if panel_mib or chunk_lanes:
+            self.tune(panel_mib, chunk_lanes)
         self.bind(F_max, stream)
 
     def bind(self, F_max, stream=None):
@@ -119,6 +129,9 @@ class Graph:
         ws = _ws(nbytes, self.device)
         B.check(L.mggcn_graph_bind(self.handle, F_max, _ws_ptr(ws), nbytes, _stream(stream)))
         self.ws, self.F_max = ws, F_max
+
+    def tune(self, panel_mib=0, chunk_lanes=0):
+        B.check(B.lib().mggcn_graph_tune(self.handle, int(panel_mib), int(chunk_lanes)))
 
     def panels(self, F, op=OP_N) -> int:
         return B.check(B.lib().mggcn_graph_panels(self.handle, op, F))
@@ -189,8 +202,8 @@ def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=Non
     B.check(getattr(L, entry)(opA, opB, M, N, K, B.ptr(A), B.ld_of(A), B.ptr(Bm), B.ld_of(Bm), float(beta), epilogue,
                               B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, nbytes,
                               _stream(stream)))
-    if ws is not None and stream is None:
-        torch.cuda.current_stream().synchronize()
+    if ws is not None:
+        _sync(stream)
     return Cm
 
 
@@ -217,8 +230,7 @@ def mggcn_softmax_ce(logits, labels, dlogits=None, stream=None):
     loss = torch.empty(1, dtype=torch.float32, device=logits.device)
     B.check(L.mggcn_softmax_ce(n, Cn, B.ptr(logits), B.ld_of(logits), B.ptr(labels), B.ptr(loss), B.ptr(dlogits),
                                B.ld_of(dlogits), _ws_ptr(ws), nbytes, _stream(stream)))
-    if stream is None:
-        torch.cuda.current_stream().synchronize()
+    _sync(stream)
     return loss, dlogits
 
 

@@ -9,6 +9,7 @@ namespace mggcn {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kMaxLossPartials = 4096;
 
 __global__ __launch_bounds__(kThreads) void relu_bwd_kernel(int64_t rows, int cols,
                                                              const float* __restrict__ act,
@@ -184,7 +185,38 @@ int team_lanes(int C) {
 
 int64_t loss_blocks(int64_t n, int C) {
   const int rows_per_block = (kThreads / 64) * (64 / team_lanes(C));
-  return std::min<int64_t>(ceil_div(n, rows_per_block), 4096);
+  return std::min<int64_t>(ceil_div(n, rows_per_block), kMaxLossPartials);
+}
+
+int softmax_ce_check(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels,
+                     const float* loss_dev, const float* dlogits, int64_t ldd) {
+  MGGCN_REQUIRE(n > 0 && C > 0, MGGCN_E_INVALID_ARG, "need n > 0 and C > 0 (n=%lld, C=%d)", (long long)n, C);
+  MGGCN_REQUIRE(ld >= C && ldd >= C, MGGCN_E_INVALID_ARG, "leading dimension < C");
+  MGGCN_REQUIRE(logits && labels && loss_dev && dlogits, MGGCN_E_INVALID_ARG, "NULL argument");
+  return MGGCN_OK;
+}
+
+// The two launches of the loss: per-workgroup partials into block_loss (every entry below `blocks`
+// is written, none is read before), then their sum in a fixed order.
+int softmax_ce_run(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels, float* loss_dev,
+                   float* dlogits, int64_t ldd, float* block_loss, hipStream_t s) {
+  const int64_t blocks = loss_blocks(n, C);
+  const int T = team_lanes(C);
+  const float inv_n = (float)(1.0 / (double)n);
+  switch ((int)ceil_div(C, T)) {  // elements per lane
+    case 1: softmax_ce_rows<1><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 2: softmax_ce_rows<2><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 3: softmax_ce_rows<3><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 4: softmax_ce_rows<4><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    case 5: case 6: case 7: case 8:
+      softmax_ce_rows<8><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
+    default:  // more than 512 classes: the general kernel walks the row in passes
+      softmax_ce_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss);
+  }
+  MGGCN_LAUNCH_CHECK();
+  loss_finish<<<1, kThreads, 0, s>>>(blocks, block_loss, 1.0 / (double)n, loss_dev);
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
 }
 
 }  // namespace
@@ -234,33 +266,13 @@ size_t mggcn_softmax_ce_workspace_bytes(int64_t n) {
 int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels,
                      float* loss_dev, float* dlogits, int64_t ldd, void* ws, size_t ws_bytes,
                      void* stream) {
-  MGGCN_REQUIRE(n > 0 && C > 0, MGGCN_E_INVALID_ARG, "need n > 0 and C > 0 (n=%lld, C=%d)", (long long)n, C);
-  MGGCN_REQUIRE(ld >= C && ldd >= C, MGGCN_E_INVALID_ARG, "leading dimension < C");
-  MGGCN_REQUIRE(logits && labels && loss_dev && dlogits, MGGCN_E_INVALID_ARG, "NULL argument");
+  const int rc = softmax_ce_check(n, C, logits, ld, labels, loss_dev, dlogits, ldd);
+  if (rc) return rc;
   MGGCN_REQUIRE(ws && aligned(ws, kWsAlign), MGGCN_E_WORKSPACE, "workspace is NULL or not 256-byte aligned");
   MGGCN_REQUIRE(ws_bytes >= mggcn_softmax_ce_workspace_bytes(n), MGGCN_E_WORKSPACE,
                 "workspace too small: %zu bytes given, %zu needed", ws_bytes,
                 mggcn_softmax_ce_workspace_bytes(n));
-  const int64_t blocks = loss_blocks(n, C);
-  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "too many rows for one launch");
-  hipStream_t s = as_stream(stream);
-  float* block_loss = static_cast<float*>(ws);
-  const int T = team_lanes(C);
-  const float inv_n = (float)(1.0 / (double)n);
-  switch ((int)ceil_div(C, T)) {  // elements per lane
-    case 1: softmax_ce_rows<1><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
-    case 2: softmax_ce_rows<2><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
-    case 3: softmax_ce_rows<3><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
-    case 4: softmax_ce_rows<4><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
-    case 5: case 6: case 7: case 8:
-      softmax_ce_rows<8><<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss); break;
-    default:  // more than 512 classes: the general kernel walks the row in passes
-      softmax_ce_kernel<<<(unsigned)blocks, kThreads, 0, s>>>(n, C, T, logits, ld, labels, dlogits, ldd, inv_n, block_loss);
-  }
-  MGGCN_LAUNCH_CHECK();
-  loss_finish<<<1, kThreads, 0, s>>>(blocks, block_loss, 1.0 / (double)n, loss_dev);
-  MGGCN_LAUNCH_CHECK();
-  return MGGCN_OK;
+  return softmax_ce_run(n, C, logits, ld, labels, loss_dev, dlogits, ldd, static_cast<float*>(ws), as_stream(stream));
 }
 
 }  // extern "C"

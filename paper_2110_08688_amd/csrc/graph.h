@@ -42,34 +42,6 @@ struct TaskSet {
   FixRow* d_fix = nullptr;
 };
 
-// "Sweep" form of the operator for dense-ish graphs: rows are dealt to teams of R rows with
-// equal entry totals, and each team's entries are stored contiguously, ordered by (column panel,
-// row of the team, column).  A team streams through its entries once, holding its R output rows
-// on chip; all teams advance through the panels at the same pace, so everything in flight
-// gathers from the same narrow slice of X.  The local row (0..R-1) rides in the top 4 bits of
-// the column word.
-struct SweepSet {
-  int32_t n_panels = 0;  // 0: not built
-  int32_t R = 8;
-  int64_t n_teams = 0;                // padded to a multiple of 256
-  std::vector<uint32_t> scol;         // column | local row << 28
-  std::vector<float> sval;
-  std::vector<int32_t> team_begin;    // n_teams + 1 offsets into scol / sval
-  std::vector<int32_t> slot_row;      // n_teams * R: output row, or -1 for an unused slot
-  std::vector<int32_t> slot_out;      // < 0: result goes to Y; else partial-sum index (piece of a cut row)
-  std::vector<FixRow> fix;            // rows cut into several slots
-  int64_t n_slots = 0;
-  uint32_t* d_scol = nullptr;
-  float* d_sval = nullptr;
-  int32_t* d_team_begin = nullptr;
-  int32_t* d_slot_row = nullptr;
-  int32_t* d_slot_out = nullptr;
-  FixRow* d_fix = nullptr;
-};
-constexpr int kSweepRowBits = 4;
-constexpr uint32_t kSweepColMask = (1u << (32 - kSweepRowBits)) - 1;
-constexpr int64_t kSweepTeamPad = 256;
-
 struct Orientation {
   int32_t n_rows = 0, n_cols = 0;
   int64_t nnz = 0;
@@ -81,16 +53,7 @@ struct Orientation {
   // Column-panel forms: either the one panel count the caller asked for, or one per power of two
   // up to what the average row length affords; a product picks by the size of its gathered operand.
   std::vector<TaskSet> panelled;
-  SweepSet sweep;    // absent unless the graph is dense enough
 };
-
-// spmm_sweep.hip
-void build_sweep_set(SweepSet* ss, int32_t n_rows, int32_t n_cols, const int32_t* rowptr, const int32_t* colidx,
-                     const float* val, int32_t n_panels, int32_t rows_per_team);
-// Launches the sweep kernel (aligned 16-byte path only).  Returns MGGCN_E_UNSUPPORTED when no
-// instantiation fits, so the caller can fall back to the task kernels.
-int launch_sweep(const SweepSet& ss, const float* X, int64_t ldx, int F, int lpr, int n_chunks, float beta,
-                 int epi, float* Y, int64_t ldy, float* partial, int64_t ldp, void* stream);
 
 }  // namespace mggcn
 
@@ -105,5 +68,4 @@ struct mggcn_graph {
   int32_t chunk_lanes = 0;     // forced lanes per feature chunk (0 = widest)
   int64_t panel_bytes = 0;      // one column panel of the gathered operand should be about this large
   bool panels_fixed = false;    // the caller chose the panel count: use it whatever the operand size
-  bool sweep_forced = false;    // sweep form requested explicitly: use it whatever the operand size
 };

@@ -111,7 +111,6 @@ int mggcn_model_create(const mggcn_graph* g, int32_t L, const int32_t* dims, con
     m->cache_input = (flags & MGGCN_MODEL_CACHE_INPUT) != 0;
     m->gather_bf16 = (flags & MGGCN_MODEL_GATHER_BF16) != 0;
     m->gemm_pieces = (flags & MGGCN_MODEL_GEMM_BF16X3) != 0;
-    m->gemm_pieces = (flags & MGGCN_MODEL_GEMM_BF16X3) != 0;
     m->dims.assign(dims, dims + L + 1);
     m->orders.resize(L);
     m->ld_act.resize(L);
@@ -261,6 +260,10 @@ int mggcn_layer_bwd(mggcn_model* m, int32_t l, const float* H_in, int64_t ld_in,
   MGGCN_REQUIRE(!H_G || ldhg >= d_in, MGGCN_E_INVALID_ARG, "ldhg < %d", d_in);
   MGGCN_REQUIRE(hg_relu_mask || H_G == nullptr || H_in == nullptr || H_G != H_in, MGGCN_E_INVALID_ARG,
                 "H_G may alias H_in only with hg_relu_mask set");
+  // The shared temporary is sized without d_0 for a cached first layer (U = Z_G W^T would need
+  // n x d_0 of it): the input features take no gradient there.
+  MGGCN_REQUIRE(!(cached && H_G), MGGCN_E_INVALID_ARG,
+                "layer 0 of a MGGCN_MODEL_CACHE_INPUT model forms no gradient with respect to X: pass H_G = NULL");
   if (act) {  // Eq. 8, unfused
     rc = mggcn_relu_bwd(m->n, d_out, act, ld_act, G, ldg, stream);
     if (rc) return rc;

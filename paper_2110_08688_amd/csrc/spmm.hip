@@ -229,17 +229,9 @@ int launch_any_f32(int vw, int lpr, const LaunchArgs& a) {
   return fail(MGGCN_E_UNSUPPORTED, "no SpMM kernel for vector width %d", vw);
 }
 
-struct SweepCarve {
-  uint32_t* scol;
-  float* sval;
-  int32_t *team_begin, *slot_row, *slot_out;
-  FixRow* fix;
-};
-
 struct GraphCarve {
   std::vector<Task*> tasks[2];   // per orientation: flat form first, then the panel forms
   std::vector<FixRow*> fix[2];
-  SweepCarve sweep[2];
   float* partial;
   int64_t ldp;
 };
@@ -258,61 +250,11 @@ size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* ou
       gc.fix[o].push_back(c.take<FixRow>(ts->fix.size() + 1));
       slots = std::max(slots, ts->n_slots);
     }
-    const SweepSet& sw = os[o]->sweep;
-    if (sw.n_panels > 0) {
-      gc.sweep[o].scol = c.take<uint32_t>(sw.scol.size() + 64);  // slack: the stream prefetch reads ahead
-      gc.sweep[o].sval = c.take<float>(sw.sval.size() + 64);
-      gc.sweep[o].team_begin = c.take<int32_t>(sw.team_begin.size());
-      gc.sweep[o].slot_row = c.take<int32_t>(sw.slot_row.size());
-      gc.sweep[o].slot_out = c.take<int32_t>(sw.slot_out.size());
-      gc.sweep[o].fix = c.take<FixRow>(sw.fix.size() + 1);
-      slots = std::max(slots, sw.n_slots);
-    }
   }
   gc.ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
   gc.partial = c.take<float>((size_t)(slots * gc.ldp) + 64);
   if (out) *out = std::move(gc);
   return c.off;
-}
-
-// Sweep form is worth building when rows are long (the team streams stay long compared with the
-// per-row bookkeeping) and X is far larger than L2.
-bool sweep_pays(int32_t n_rows, int32_t n_cols, int64_t nnz) {
-  return n_rows > 0 && nnz / n_rows >= 64 && (int64_t)n_cols * 512 >= (24ll << 20) &&
-         (int64_t)n_cols <= (int64_t)kSweepColMask;
-}
-
-int32_t default_sweep_panels(int32_t n_cols) {
-  if (const char* e = std::getenv("MGGCN_SWEEP_PANELS")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 4096) return v;
-  }
-  // one panel of X at a reference width of 128 floats ~ 2 MB: a few panels fit one 4 MB L2
-  int64_t p = 1;
-  while (p * (2ll << 20) < (int64_t)n_cols * 512) p <<= 1;
-  return (int32_t)std::min<int64_t>(p, 1024);
-}
-
-int32_t default_sweep_rows() {
-  if (const char* e = std::getenv("MGGCN_SWEEP_R")) {
-    const int v = std::atoi(e);
-    if (v == 4 || v == 8 || v == 16) return v;
-  }
-  return 8;
-}
-
-int build_sweep_for(Orientation* o, int32_t n_panels, int32_t rows_per_team, hipStream_t s) {
-  MGGCN_REQUIRE(!o->wide, MGGCN_E_UNSUPPORTED, "the sweep form is built from 32-bit row offsets only");
-  std::vector<int32_t> rp((size_t)o->n_rows + 1), ci((size_t)o->nnz);
-  std::vector<float> va((size_t)o->nnz);
-  MGGCN_HIP(hipMemcpyAsync(rp.data(), o->rowptr, sizeof(int32_t) * rp.size(), hipMemcpyDeviceToHost, s));
-  if (o->nnz > 0) {
-    MGGCN_HIP(hipMemcpyAsync(ci.data(), o->colidx, sizeof(int32_t) * ci.size(), hipMemcpyDeviceToHost, s));
-    MGGCN_HIP(hipMemcpyAsync(va.data(), o->val, sizeof(float) * va.size(), hipMemcpyDeviceToHost, s));
-  }
-  MGGCN_HIP(hipStreamSynchronize(s));
-  build_sweep_set(&o->sweep, o->n_rows, o->n_cols, rp.data(), ci.data(), va.data(), n_panels, rows_per_team);
-  return MGGCN_OK;
 }
 
 }  // namespace
@@ -336,13 +278,7 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
                 "a %d x %d matrix cannot be declared symmetric: pass its transpose", n_rows, n_cols);
   MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 64, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 64]",
                 n_panels);
-  if (seg_len == 0) {
-    seg_len = kDefaultSegLen;
-    if (const char* e = std::getenv("MGGCN_SEG_LEN")) {
-      const int v = std::atoi(e);
-      if (v >= 8 && v <= (1 << 20)) seg_len = v;
-    }
-  }
+  if (seg_len == 0) seg_len = kDefaultSegLen;
   seg_len = std::max(seg_len, 8);
   hipStream_t s = as_stream(stream);
 
@@ -352,20 +288,6 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
   g->seg_len = seg_len;
   g->panel_bytes = 16ll << 20;
   g->panels_fixed = n_panels > 1;
-  if (const char* e = std::getenv("MGGCN_CHUNK_LANES")) {
-    const int v = std::atoi(e);
-    if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) g->chunk_lanes = v;
-  }
-  if (const char* e = std::getenv("MGGCN_PANEL_MB")) {
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= (1 << 20)) g->panel_bytes = (int64_t)v << 20;
-  }
-  if (n_panels == 0)
-    if (const char* e = std::getenv("MGGCN_PANELS")) {
-      const int v = std::atoi(e);
-      if (v >= 1 && v <= 64) { n_panels = v; g->panels_fixed = v > 1; }
-    }
-
   auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const IT* rp, const int32_t* ci,
                    const float* va) -> int {
     o->n_rows = nr; o->n_cols = nc; o->rowptr = rp; o->wide = sizeof(IT) == 8; o->colidx = ci; o->val = va;
@@ -419,10 +341,6 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
         build_task_set(&o->panelled.back(), nr, h, cuts, n_cuts, Pmax / P, P, seg_len);
       }
     }
-    // The sweep form measured slower than the panel launches on MI355X (its teams drift apart
-    // and lose the shared panel), so it is built only on request.
-    if (n_panels == 0 && sweep_pays(nr, nc, o->nnz) && std::getenv("MGGCN_SWEEP"))
-      return build_sweep_for(o, default_sweep_panels(nc), default_sweep_rows(), s);
     return MGGCN_OK;
   };
   int rc = guarded([&] { return setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val); });
@@ -460,7 +378,11 @@ int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, in
   MGGCN_REQUIRE(Y != nullptr, MGGCN_E_INVALID_ARG, "Y is NULL");
   if (X != nullptr && o.n_cols > 0) {  // rows of Y are written while rows of X are still being gathered
     const char* xb = static_cast<const char*>(X);
-    const char* xe = xb + ((size_t)(o.n_cols - 1) * (size_t)ldx + (size_t)F) * (size_t)elem_bytes;
+    // the wide gather path reads whole 16-byte vectors: a row of X is read up to F rounded up to
+    // 4 floats (8 bfloat16), which lies inside its leading dimension
+    const size_t per_vec = 16 / (size_t)elem_bytes;
+    const size_t x_cols = std::min<size_t>((size_t)ldx, align_up((size_t)F, per_vec));
+    const char* xe = xb + ((size_t)(o.n_cols - 1) * (size_t)ldx + x_cols) * (size_t)elem_bytes;
     const char* yb = reinterpret_cast<const char*>(Y);
     const char* ye = yb + ((size_t)(o.n_rows - 1) * (size_t)ldy + (size_t)F) * sizeof(float);
     MGGCN_REQUIRE(xe <= yb || ye <= xb, MGGCN_E_INVALID_ARG, "X and Y overlap");
@@ -615,23 +537,6 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
                                    hipMemcpyHostToDevice, s));
       }
     }
-    for (int o = 0; o < 2; ++o) {
-      if (!os[o] || os[o]->sweep.n_panels == 0) continue;
-      SweepSet& sw = os[o]->sweep;
-      sw.d_scol = gc.sweep[o].scol; sw.d_sval = gc.sweep[o].sval; sw.d_team_begin = gc.sweep[o].team_begin;
-      sw.d_slot_row = gc.sweep[o].slot_row; sw.d_slot_out = gc.sweep[o].slot_out; sw.d_fix = gc.sweep[o].fix;
-      auto up = [&](void* dst, const void* src, size_t bytes) -> int {
-        if (bytes) MGGCN_HIP(hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, s));
-        return MGGCN_OK;
-      };
-      int rc = up(sw.d_scol, sw.scol.data(), sizeof(uint32_t) * sw.scol.size());
-      if (!rc) rc = up(sw.d_sval, sw.sval.data(), sizeof(float) * sw.sval.size());
-      if (!rc) rc = up(sw.d_team_begin, sw.team_begin.data(), sizeof(int32_t) * sw.team_begin.size());
-      if (!rc) rc = up(sw.d_slot_row, sw.slot_row.data(), sizeof(int32_t) * sw.slot_row.size());
-      if (!rc) rc = up(sw.d_slot_out, sw.slot_out.data(), sizeof(int32_t) * sw.slot_out.size());
-      if (!rc) rc = up(sw.d_fix, sw.fix.data(), sizeof(FixRow) * sw.fix.size());
-      if (rc) return rc;
-    }
     MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
     g->d_partial = gc.partial;
     g->ldp = gc.ldp;
@@ -646,25 +551,16 @@ int mggcn_graph_destroy(mggcn_graph* g) {
   return MGGCN_OK;
 }
 
-int mggcn_graph_build_sweep(mggcn_graph* g, int32_t n_panels, int32_t rows_per_team, void* stream) {
+int mggcn_graph_tune(mggcn_graph* g, int32_t panel_mib, int32_t chunk_lanes) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
-  MGGCN_REQUIRE(n_panels >= 0 && n_panels <= 4096, MGGCN_E_INVALID_ARG, "n_panels %d outside [0, 4096]", n_panels);
-  MGGCN_REQUIRE(rows_per_team == 0 || rows_per_team == 4 || rows_per_team == 8 || rows_per_team == 16,
-                MGGCN_E_INVALID_ARG, "rows_per_team must be 0 (default), 4, 8 or 16");
-  MGGCN_REQUIRE((int64_t)g->fwd.n_cols <= (int64_t)kSweepColMask && (int64_t)g->fwd.n_rows <= (int64_t)kSweepColMask,
-                MGGCN_E_UNSUPPORTED, "sweep form holds column indices in 28 bits");
-  hipStream_t s = as_stream(stream);
-  Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
-  for (int o = 0; o < 2; ++o) {
-    if (!os[o]) continue;
-    const int rc = guarded([&] {
-      return build_sweep_for(os[o], n_panels > 0 ? n_panels : default_sweep_panels(os[o]->n_cols),
-                             rows_per_team > 0 ? rows_per_team : default_sweep_rows(), s);
-    });
-    if (rc) return rc;
-  }
-  g->sweep_forced = true;
-  g->bound = false;  // the tables changed: bind again
+  MGGCN_REQUIRE(panel_mib >= 0 && panel_mib <= (1 << 20), MGGCN_E_INVALID_ARG, "panel_mib %d outside [0, 2^20]",
+                panel_mib);
+  const bool lanes_ok = chunk_lanes == -1 || chunk_lanes == 0 ||
+                        (chunk_lanes >= 1 && chunk_lanes <= 64 && (chunk_lanes & (chunk_lanes - 1)) == 0);
+  MGGCN_REQUIRE(lanes_ok, MGGCN_E_INVALID_ARG, "chunk_lanes %d is not -1, 0 or a power of two up to 64", chunk_lanes);
+  if (panel_mib > 0) g->panel_bytes = (int64_t)panel_mib << 20;
+  if (chunk_lanes == -1) g->chunk_lanes = 0;
+  else if (chunk_lanes > 0) g->chunk_lanes = chunk_lanes;
   return MGGCN_OK;
 }
 
@@ -673,8 +569,6 @@ int mggcn_graph_panels(const mggcn_graph* g, int op, int32_t F) {
   MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
   MGGCN_REQUIRE(F >= 0, MGGCN_E_INVALID_ARG, "F = %d is negative", F);
   const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
-  const bool big = (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes;
-  if (o.sweep.n_panels > 0 && (g->sweep_forced || big)) return 1;  // sweep form: one launch
   int64_t slice = F;
   const TaskSet& ts = plan_passes(g, o, F, (int)sizeof(float), MGGCN_EPI_NONE, &slice);
   return (int)(ts.n_panels * ceil_div(std::max(F, 1), slice));
@@ -691,24 +585,6 @@ int mggcn_spmm(const mggcn_graph* g, int op, const float* X, int64_t ldx, int32_
   if (aligned(X, 16) && aligned(Y, 16) && ldx % 4 == 0 && ldy % 4 == 0) vw = 4;
   else if (aligned(X, 8) && aligned(Y, 8) && ldx % 2 == 0 && ldy % 2 == 0) vw = 2;
 
-  // Sweep form (one launch, every row of Y written once) where it was built and X is large.
-  int lpr = std::min(64, pow2_ceil((int)ceil_div(F, vw)));
-  if (g->chunk_lanes > 0) lpr = std::min(lpr, g->chunk_lanes);
-  if (o.sweep.n_panels > 0 && vw == 4 && lpr >= 4 &&
-      (g->sweep_forced || (int64_t)o.n_cols * F * (int64_t)sizeof(float) > g->panel_bytes)) {
-    const int n_chunks = (int)ceil_div(F, lpr * vw);
-    const SweepSet& sw = o.sweep;
-    rc = launch_sweep(sw, X, ldx, F, lpr, n_chunks, beta, epilogue, Y, ldy, g->d_partial, g->ldp, stream);
-    if (rc == MGGCN_OK) {
-      if (!sw.fix.empty()) {
-        spmm_fixup<<<(unsigned)sw.fix.size(), kThreads, 0, as_stream(stream)>>>(
-            sw.d_fix, (int64_t)sw.fix.size(), g->d_partial, g->ldp, F, beta, epilogue, Y, ldy);
-        MGGCN_LAUNCH_CHECK();
-      }
-      return MGGCN_OK;
-    }
-    if (rc != MGGCN_E_UNSUPPORTED) return rc;
-  }
   return spmm_run(g, o, X, ldx, (int)sizeof(float), vw, F, beta, epilogue, Y, ldy, stream, launch_any_f32);
 }
 

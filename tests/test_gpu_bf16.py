@@ -304,6 +304,19 @@ def manual_epoch(mg, model, Xd, labels_d, Wd, cached=False):
     return loss, WG, masks, fwd, bwd
 
 
+def assert_bf16_relu_decisions_agree(ref, n, rp, ci, v64, W64s, r_orders, fwd_codes, masks, what):
+    """The ReLU' decisions handed to the oracle, bounded as in the fp32 tests: the oracle's fp64
+    pre-activation of every hidden layer, formed from the same bfloat16 operand the device gathered,
+    must take the same decision except at entries that are zero to within fp32 rounding."""
+    from test_gpu_parity import assert_relu_decisions_agree
+
+    Zs = []
+    for l in range(len(W64s) - 1):
+        P = ref.spmm(ref.OP_N, n, n, rp, ci, v64, values_of(fwd_codes[l]).astype(np.float64))
+        Zs.append(P if r_orders[l] == ref.GEMM_FIRST else ref.gemm(ref.OP_N, ref.OP_N, P, W64s[l]))
+    return assert_relu_decisions_agree(masks, Zs, what)
+
+
 def assert_operands_are_roundings(dev_codes, own_codes, what):
     """The device's operand is the rounding of its fp32 value, the oracle's that of its fp64 value: they
     agree except where the value sits within fp32 rounding of a boundary (then they are neighbours)."""
@@ -340,6 +353,8 @@ def run_epoch_case(mg, dev, ref, g, dims, orders, seed, cached=False):
         assert np.array_equal(WG[l].cpu().numpy(), WG2[l].cpu().numpy()), "epoch must be reproducible bit for bit"
         assert np.array_equal(WG[l].cpu().numpy(), mWG[l].cpu().numpy()), "layer-by-layer epoch differs"
     r_orders = [ref.SPMM_FIRST if model.order(l) == mg.ORDER_SPMM_FIRST else ref.GEMM_FIRST for l in range(L)]
+    assert_bf16_relu_decisions_agree(ref, n, rp, ci, val.astype(np.float64), [w.astype(np.float64) for w in Ws], r_orders,
+                                     fwd, masks, "bf16 epoch")
     rl, rWG, own_f, own_b = ref.epoch_bf16(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
                                            [w.astype(np.float64) for w in Ws], orders=r_orders, relu_masks=masks,
                                            fwd_codes=fwd, bwd_codes=bwd)
@@ -411,7 +426,7 @@ def test_model_bf16_flag_errors(mg, dev, ref):
 
 
 @pytest.mark.parametrize("F", [100, 256, 602])
-def test_spmm_automatic_panels_and_feature_slices(mg, dev, ref, monkeypatch, F):
+def test_spmm_automatic_panels_and_feature_slices(mg, dev, ref, F):
     """Automatic mode on a graph dense enough to get panel forms, with the per-panel target shrunk
     to 1 MiB so that a small operand already takes several panels and, at the wider widths,
     several feature slices -- the path a wide operand takes on the 233K-vertex graph."""
@@ -419,9 +434,7 @@ def test_spmm_automatic_panels_and_feature_slices(mg, dev, ref, monkeypatch, F):
     g = wl.chung_lu(3000, 600e3, 2.1, 1500.0, 41)
     rp, ci, val = normalized(ref, g)
     n = g.n_rows
-    monkeypatch.setenv("MGGCN_PANEL_MB", "1")
-    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=F)
-    monkeypatch.delenv("MGGCN_PANEL_MB")
+    G = mg.Graph(n, n, to_dev(rp, dev), to_dev(ci, dev), to_dev(val, dev), F_max=F, panel_mib=1)
     # the fp32 target is 3/4 of the setting, feature slices are cut for 2/3 of that; 200 entries per
     # row afford 4 panels; 7 MiB at F=602 then also takes 4 feature slices
     assert G.panels(602) == 16 and G.panels(100) == 2 and G.panels(16) == 1

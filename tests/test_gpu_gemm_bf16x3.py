@@ -7,7 +7,8 @@ import numpy as np
 import pytest
 
 import workloads as wl
-from test_gpu_parity import (TOL, _model_inputs, assert_rows_close, dev, gpu_relu_decisions, mg, normalized,  # noqa: F401
+from test_gpu_parity import (TOL, _model_inputs, assert_relu_decisions_agree, assert_rows_close, dev, gpu_relu_decisions, mg,  # noqa: F401
+                             normalized, oracle_preactivations,
                              row_err, say, to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -147,6 +148,8 @@ def test_epoch_with_gemm_bf16x3(mg, dev, ref, cfg_name, dims, flags):
     loss2, WG2 = mg.mggcn_epoch(model, Xd, ld, Wd)
     masks = gpu_relu_decisions(mg, model, Xd, Wd)
     r_ords = [ref.SPMM_FIRST if model.order(l) == mg.ORDER_SPMM_FIRST else ref.GEMM_FIRST for l in range(L)]
+    assert_relu_decisions_agree(masks, oracle_preactivations(ref, n, rp, ci, val.astype(np.float64), X.astype(np.float64),
+                                                             [w.astype(np.float64) for w in Ws], r_ords), "gemm bf16x3")
     rl, rWG, _ = ref.epoch(n, rp, ci, val.astype(np.float64), X.astype(np.float64), labels,
                            [w.astype(np.float64) for w in Ws], orders=r_ords, relu_masks=masks)
     assert abs(loss.item() - rl) <= 1e-5 * abs(rl)
