@@ -189,7 +189,15 @@ def mggcn_spmm_bf16(graph: Graph, op, Xb, F=None, beta=0.0, epilogue=EPI_NONE, Y
 # GeMM, ReLU', loss
 # ------------------------------------------------------------------------------------------
 
-def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None, entry="mggcn_gemm"):
+def gemm_workspace(opA, opB, M, N, K, device):
+    """A workspace tensor for repeated mggcn_gemm calls of one shape (None if the shape needs none)."""
+    nbytes = B.lib().mggcn_gemm_workspace_bytes(opA, opB, M, N, K)
+    return _ws(nbytes, device) if nbytes else None
+
+
+def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None, entry="mggcn_gemm", ws=None):
+    """ws: a tensor from gemm_workspace() that the caller keeps alive; without it a workspace is allocated for
+    this call and the stream is drained before it is dropped."""
     torch = _torch()
     L = B.lib()
     M = A.shape[0] if opA == OP_N else A.shape[1]
@@ -198,18 +206,21 @@ def mggcn_gemm(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=Non
     if Cm is None:
         Cm = torch.empty((M, N), dtype=torch.float32, device=A.device)
     nbytes = L.mggcn_gemm_workspace_bytes(opA, opB, M, N, K)
-    ws = _ws(nbytes, A.device) if nbytes else None
+    own = ws is None and nbytes > 0
+    if own:
+        ws = _ws(nbytes, A.device)
+    ws_bytes = 0 if ws is None else ws.numel() - (_ws_ptr(ws) - ws.data_ptr())
     B.check(getattr(L, entry)(opA, opB, M, N, K, B.ptr(A), B.ld_of(A), B.ptr(Bm), B.ld_of(Bm), float(beta), epilogue,
-                              B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, nbytes,
+                              B.ptr(Cm), B.ld_of(Cm), _ws_ptr(ws) if ws is not None else None, ws_bytes,
                               _stream(stream)))
-    if ws is not None:
+    if own:
         _sync(stream)
     return Cm
 
 
-def mggcn_gemm_bf16x3(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None):
+def mggcn_gemm_bf16x3(opA, opB, A, Bm, beta=0.0, epilogue=EPI_NONE, Cm=None, stream=None, ws=None):
     """The same product on the bfloat16 matrix instructions (three exact pieces per operand)."""
-    return mggcn_gemm(opA, opB, A, Bm, beta=beta, epilogue=epilogue, Cm=Cm, stream=stream, entry="mggcn_gemm_bf16x3")
+    return mggcn_gemm(opA, opB, A, Bm, beta=beta, epilogue=epilogue, Cm=Cm, stream=stream, entry="mggcn_gemm_bf16x3", ws=ws)
 
 
 def mggcn_relu_bwd(act, G, stream=None):
@@ -356,3 +367,29 @@ def mggcn_epoch(model: Model, X, labels, Ws, W_Gs=None, loss=None, stream=None):
     B.check(B.lib().mggcn_epoch(model.handle, B.ptr(X), B.ld_of(X) if X is not None else 0, B.ptr(labels), Wp,
                                 B.ptr(loss), Gp, _stream(stream)))
     return loss, W_Gs
+
+
+# ------------------------------------------------------------------------------------------
+# memory-system probes (measurement aids for bench.py)
+# ------------------------------------------------------------------------------------------
+
+def mggcn_probe_read(buf, sink=None, stream=None):
+    """Read a device tensor once, contiguously (timed by the caller)."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.empty(B.lib().mggcn_probe_sink_floats(), dtype=torch.float32, device=buf.device)
+    B.check(B.lib().mggcn_probe_read(B.ptr(buf), buf.numel() * buf.element_size(), B.ptr(sink), _stream(stream)))
+    return sink
+
+
+def mggcn_probe_gather(X, idx, row_bytes=None, sink=None, stream=None):
+    """Fetch the rows idx (int32 device tensor) of the 2-D device tensor X, `row_bytes` of each."""
+    torch = _torch()
+    if sink is None:
+        sink = torch.empty(B.lib().mggcn_probe_sink_floats(), dtype=torch.float32, device=X.device)
+    stride = B.ld_of(X) * X.element_size()
+    if row_bytes is None:
+        row_bytes = X.shape[1] * X.element_size()
+    B.check(B.lib().mggcn_probe_gather(B.ptr(X), X.shape[0], int(row_bytes), stride, B.ptr(idx), idx.numel(), B.ptr(sink),
+                                       _stream(stream)))
+    return sink
