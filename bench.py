@@ -50,6 +50,11 @@ NOMINAL_NNZ = {"tiny": 65_536 + 4096, "medium": 114_600_000 + 232_965, "large": 
                "block": 200_000_000, "rmat": 64_000_000 + (1 << 22), "proteins": 1_300_000_000 + 8_740_000}
 
 
+def log(msg: str) -> None:
+    """progress lines on stderr (stdout carries the one JSON line)"""
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
 def spmm_bytes(nnz: int, n_rows: int, F: int) -> int:
     """no-reuse algorithmic bytes of one SpMM"""
     return 8 * nnz + 4 * (n_rows + 1) + 4 * F * nnz + 4 * F * n_rows
@@ -111,6 +116,14 @@ def calibrate(mg, torch, dev, gib=8, reps=5):
         ms = timed(torch, lambda: mg.mggcn_probe_gather(X, idx), reps)["min"]
         out[f"random_gather_{row_bytes}B_GBps"] = round(n_idx * row_bytes / (ms * 1e-3) / 1e9, 1)
         del idx
+    # the same gather over 128 MiB: beyond the 8 x 4 MB of L2, inside the 256 MB Infinity Cache -- what L2 misses
+    # cost when the fabric-side cache serves them (the traffic counters cannot tell these from HBM reads)
+    small = buf[: 128 << 18].view(-1, 128)
+    idx = torch.randint(0, small.shape[0], ((8 << 30) // 512,), device=dev, dtype=torch.int32, generator=gen)
+    ms = timed(torch, lambda: mg.mggcn_probe_gather(small, idx), reps)["min"]
+    out["random_gather_512B_over_128MiB_GBps"] = round(idx.numel() * 512 / (ms * 1e-3) / 1e9, 1)
+    del idx, small
+    log(f"calibration {out}")
     del buf
     torch.cuda.empty_cache()
     return out
@@ -155,6 +168,7 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
     deg_row = (np.diff(g.rowptr) + 1).astype(np.int32)          # stand-in global degrees
     deg_col = (1 + 8 * col_count).astype(np.int32)
     gen_s = time.time() - t0
+    log(f"block: generated {nr} x {nc}, {g.nnz} entries in {gen_s:.1f}s")
     setup = {}
     torch.cuda.synchronize()
     t0 = time.time()
@@ -176,6 +190,7 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
     touched_fwd = nr + int(np.count_nonzero(col_count[nr:] > 0))  # columns below nr hold a diagonal entry
     touched_bwd = nr  # every row of the block holds its diagonal entry
     sha = sha256_arrays(rowptr.cpu().numpy(), colidx.cpu().numpy(), val.cpu().numpy())
+    log(f"block: setup {setup}, nnz {nnz}")
 
     gen = torch.Generator(device=dev).manual_seed(cfg.seed + 0x100)
     X = torch.randn((nc, d_in), device=dev, generator=gen)
@@ -222,9 +237,11 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
         step()
     torch.cuda.synchronize()
     step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    log(f"block: {args.steps} steps, {step_ms:.3f} ms per step")
 
     reps = max(5, args.steps)
     ops = {k: timed(torch, fn, reps) for k, fn in calls.items()}
+    log(f"block: per-call medians {({k: round(v['median'], 3) for k, v in ops.items()})}")
     fwd_ms, bwd_ms = ops[f"spmm_fwd_F{d_in}"]["median"], ops[f"spmm_bwd_F{d_in}"]["median"]
     gemm_ms = sum(v["median"] for k, v in ops.items() if k.startswith("gemm"))
     eff_f, eff_b = spmm_bytes(nnz, nr, d_in), spmm_bytes(nnz, nc, d_in)
@@ -243,6 +260,7 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline_block(np, torch, dev, rowptr, colidx, val, X, nr, nc, nnz, d_in)
+        log(f"block: cpu baseline {cpu['value']} GB/s")
 
     out = {
         "metric": "spmm_hbm_bandwidth", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -328,6 +346,7 @@ def run_epoch_config(args, name, cfg, mg, wl, torch, dev, calib, brief=False):
     Ws = [torch.from_numpy(w).to(dev) for w in cfg.weights()]
     labels = torch.from_numpy(cfg.labels(n)).to(dev)
     gen_s = time.time() - t0
+    log(f"{name}: generated n={n}, {g.nnz} entries in {gen_s:.1f}s")
 
     setup = {}
     torch.cuda.synchronize()
@@ -383,6 +402,7 @@ def run_epoch_config(args, name, cfg, mg, wl, torch, dev, calib, brief=False):
         return (time.perf_counter() - t0) * 1e3 / steps, float(loss.item())
 
     epoch_ms, loss_value = epoch_ms_of(model, X)
+    log(f"{name}: setup {setup}; epoch {epoch_ms:.3f} ms, loss {loss_value:.6f}")
 
     # ---- the same epoch with A^ X formed once outside it (X is constant across epochs)
     model_c = mg.Model(graph, dims, flags=mg.MODEL_CACHE_INPUT)
@@ -457,6 +477,7 @@ def run_epoch_config(args, name, cfg, mg, wl, torch, dev, calib, brief=False):
         dom_ms, mt.get(f"spmm_fwd_F{Fdom}"), spmm_bytes(nnz, n, Fdom), spmm_bytes_min(nnz, n, touched, Fdom), 2.0 * nnz * Fdom,
         calib, mt.get("profile"), P)
 
+    log(f"{name}: per-call timings done; oracle baseline next")
     cpu = None
     if not args.no_cpu_baseline and not brief:
         cpu = cpu_baseline_epoch(args, name, np, wl, X, rowptr, colidx, val, n, nnz, spmm_keys, cfg, labels, Ws)
