@@ -273,6 +273,22 @@ int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits /*dev*/, int64_t 
                      const int32_t* labels /*dev*/, float* loss_dev, float* dlogits /*dev*/,
                      int64_t ldd, void* ws, size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate or hand over device memory at the point of the call -- code under
+ * HIP graph capture, tight serving or training loops, harnesses that forbid hipMalloc: the same loss
+ * and gradient as mggcn_softmax_ce (same kernels, same bits), with the loss partials in a 16 KiB
+ * buffer that is part of the library's device code instead of a caller workspace.  The call makes no
+ * hipMalloc / hipFree and uses no allocating routine; it only enqueues two kernels on `stream`.
+ * Limits: n <= MGGCN_SOFTMAX_CE_STATIC_MAX_ROWS (MGGCN_E_UNSUPPORTED beyond; that many rows already
+ * fill the buffer's 4096 partials many times over).  Every call on one GPU uses that GPU's one
+ * buffer, which keeps the previous call's contents (each call overwrites the partials it then
+ * reads): calls that overlap in time on one GPU race -- keep them on one stream or order them with
+ * events.  The first call on a GPU looks up the buffer's address (hipGetSymbolAddress, no
+ * allocation): make that one outside any stream capture. */
+#define MGGCN_SOFTMAX_CE_STATIC_MAX_ROWS ((int64_t)1 << 40)
+int mggcn_softmax_ce_static(int64_t n, int32_t C, const float* logits /*dev*/, int64_t ld,
+                            const int32_t* labels /*dev*/, float* loss_dev, float* dlogits /*dev*/,
+                            int64_t ldd, void* stream);
+
 /* Adam update of one dense parameter array (the optimiser the paper trains with; it states no
  * hyper-parameters, so they are arguments).  step counts from 1.  All arrays dev, `count` fp32
  * elements, updated in place:

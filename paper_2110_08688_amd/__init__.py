@@ -245,6 +245,17 @@ def mggcn_softmax_ce(logits, labels, dlogits=None, stream=None):
     return loss, dlogits
 
 
+def mggcn_softmax_ce_static(logits, labels, loss, dlogits=None, stream=None):
+    """mggcn_softmax_ce without any allocation: the caller passes every buffer (loss: 1-element fp32 device
+    tensor), the partial sums live in the library's own built-in device buffer.  -> (loss, dlogits)"""
+    n, Cn = logits.shape
+    if dlogits is None:
+        dlogits = logits
+    B.check(B.lib().mggcn_softmax_ce_static(n, Cn, B.ptr(logits), B.ld_of(logits), B.ptr(labels), B.ptr(loss),
+                                            B.ptr(dlogits), B.ld_of(dlogits), _stream(stream)))
+    return loss, dlogits
+
+
 def mggcn_adam_step(W, G, m, v, step, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, stream=None):
     """In-place Adam update of a contiguous parameter tensor W with moments m, v."""
     assert W.is_contiguous() and G.is_contiguous() and m.is_contiguous() and v.is_contiguous()

@@ -52,6 +52,7 @@ SIGNATURES = {
     "mggcn_adam_step": (C.c_int, [_i64, _vp, _vp, _vp, _vp, _i32, _f32, _f32, _f32, _f32, _vp]),
     "mggcn_softmax_ce_workspace_bytes": (_sz, [_i64]),
     "mggcn_softmax_ce": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _sz, _vp]),
+    "mggcn_softmax_ce_static": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _vp, _vp, _i64, _vp]),
     "mggcn_model_create": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(_vp)]),
     "mggcn_model_cache_input": (C.c_int, [_vp, _vp, _i64, _vp]),
     "mggcn_model_destroy": (C.c_int, [_vp]),

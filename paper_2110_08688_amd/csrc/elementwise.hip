@@ -4,12 +4,19 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 namespace mggcn {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kMaxLossPartials = 4096;
+
+// Loss partials of mggcn_softmax_ce_static: one per workgroup of the loss kernel, whose grid never
+// exceeds this many workgroups.  The array lives in every GPU's memory from the moment the library's
+// code is loaded there until the process ends (16 KiB per GPU).  In host code the name is only a
+// handle for hipGetSymbolAddress; kernels are given the address that call returns.
+constexpr int kStaticLossPartials = 4096;
+static __device__ __align__(256) float scratch[kStaticLossPartials];
 
 __global__ __launch_bounds__(kThreads) void relu_bwd_kernel(int64_t rows, int cols,
                                                              const float* __restrict__ act,
@@ -185,7 +192,27 @@ int team_lanes(int C) {
 
 int64_t loss_blocks(int64_t n, int C) {
   const int rows_per_block = (kThreads / 64) * (64 / team_lanes(C));
-  return std::min<int64_t>(ceil_div(n, rows_per_block), kMaxLossPartials);
+  return std::min<int64_t>(ceil_div(n, rows_per_block), kStaticLossPartials);
+}
+
+// Address of `scratch` on the current device, looked up once per device (each GPU holds its own
+// copy of the array at its own address).
+int static_scratch(float** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* ptrs[kMaxDevices] = {};
+  int dev = -1;
+  MGGCN_HIP(hipGetDevice(&dev));
+  MGGCN_REQUIRE(dev >= 0 && dev < kMaxDevices, MGGCN_E_UNSUPPORTED, "device index %d outside [0, %d)", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptrs[dev] == nullptr) {
+    void* p = nullptr;
+    MGGCN_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    MGGCN_REQUIRE(p != nullptr, MGGCN_E_HIP, "hipGetSymbolAddress returned a null address");
+    ptrs[dev] = static_cast<float*>(p);
+  }
+  *out = ptrs[dev];
+  return MGGCN_OK;
 }
 
 int softmax_ce_check(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels,
@@ -273,6 +300,22 @@ int mggcn_softmax_ce(int64_t n, int32_t C, const float* logits, int64_t ld, cons
                 "workspace too small: %zu bytes given, %zu needed", ws_bytes,
                 mggcn_softmax_ce_workspace_bytes(n));
   return softmax_ce_run(n, C, logits, ld, labels, loss_dev, dlogits, ldd, static_cast<float*>(ws), as_stream(stream));
+}
+
+int mggcn_softmax_ce_static(int64_t n, int32_t C, const float* logits, int64_t ld, const int32_t* labels,
+                            float* loss_dev, float* dlogits, int64_t ldd, void* stream) {
+  int rc = softmax_ce_check(n, C, logits, ld, labels, loss_dev, dlogits, ldd);
+  if (rc) return rc;
+  MGGCN_REQUIRE(n <= MGGCN_SOFTMAX_CE_STATIC_MAX_ROWS, MGGCN_E_UNSUPPORTED,
+                "n = %lld exceeds the %lld rows mggcn_softmax_ce_static takes; use mggcn_softmax_ce with a workspace",
+                (long long)n, (long long)MGGCN_SOFTMAX_CE_STATIC_MAX_ROWS);
+  MGGCN_REQUIRE(loss_blocks(n, C) <= kStaticLossPartials, MGGCN_E_UNSUPPORTED,
+                "the loss needs %lld partial sums, the built-in buffer holds %d", (long long)loss_blocks(n, C),
+                kStaticLossPartials);
+  float* partials = nullptr;
+  rc = static_scratch(&partials);
+  if (rc) return rc;
+  return softmax_ce_run(n, C, logits, ld, labels, loss_dev, dlogits, ldd, partials, as_stream(stream));
 }
 
 }  // extern "C"
