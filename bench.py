@@ -40,7 +40,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # counters sit between L2 and the fabric: fills served by the 256 MB Infinity Cache are included, so
 # the figure is an upper bound of the HBM traffic.
 MEASURED_TRAFFIC = {
-    "block": {"profile": None, "spmm_fwd": None, "spmm_bwd": None},
+    "block": {"profile": "profiles/spmm_block_F128_pmc.md", "spmm_fwd": 97_505_427_302, "spmm_bwd": 165_822_886_817},
     "large": {"profile": "profiles/spmm_large_pmc.md", "spmm_fwd_F256": 129_270_000_000, "spmm_fwd_F100": 63_700_000_000,
               "spmm_fwd_F47": 31_500_000_000},
     "medium": {"profile": "profiles/spmm_medium_F128_pmc.md", "spmm_fwd_F128": 17_018_680_064},
@@ -123,6 +123,11 @@ def calibrate(mg, torch, dev, gib=8, reps=5):
     ms = timed(torch, lambda: mg.mggcn_probe_gather(small, idx), reps)["min"]
     out["random_gather_512B_over_128MiB_GBps"] = round(idx.numel() * 512 / (ms * 1e-3) / 1e9, 1)
     del idx, small
+    # the fp32 matrix instruction on register operands: what the matrix pipes sustain with nothing else going on
+    sink = torch.empty(4096, dtype=torch.float32, device=dev)
+    flop = mg.mggcn_probe_mfma(20000, sink)
+    ms = timed(torch, lambda: mg.mggcn_probe_mfma(20000, sink), 3, warm=1)["min"]
+    out["mfma_f32_registers_only_TFLOPs"] = round(flop / (ms * 1e-3) / 1e12, 1)
     log(f"calibration {out}")
     del buf
     torch.cuda.empty_cache()

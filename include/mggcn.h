@@ -127,16 +127,22 @@ int mggcn_csr_normalize64(int32_t n_rows, int32_t n_cols, const int64_t* rowptr_
                           float* val_out /*dev*/, void* ws, size_t ws_bytes, void* stream);
 
 /* Explicit transpose of a CSR matrix (the paper keeps A^ and A^^T both, for the backward
- * SpMM of Eq. 9).  Rows of the result have ascending columns; the result is unique, so it
- * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries.  32-bit row offsets only
- * (fewer than 2^31 entries).  The input must be a well-formed CSR (what mggcn_csr_normalize
- * writes): nothing is validated here; a column index outside [0, n_cols) is never followed, but
- * the result is then meaningless. */
+ * SpMM of Eq. 9): a counting sort by column -- integer histogram, prefix sum, stable radix sort of the
+ * entry positions.  Rows of the result have ascending columns; the result is unique, so it
+ * is bit-reproducible.  All arrays dev; rowptr_t has n_cols+1 entries.  The input must be a
+ * well-formed CSR (what mggcn_csr_normalize writes): nothing is validated here; a column index
+ * outside [0, n_cols) is never followed, but the result is then meaningless.
+ * _transpose64 takes and writes 64-bit row offsets (fewer than 2^32 entries); the 32-bit form
+ * returns MGGCN_E_OVERFLOW from 2^31 - 1 entries on.  One workspace size serves both. */
 size_t mggcn_csr_transpose_workspace_bytes(int32_t n_rows, int32_t n_cols, int64_t nnz);
 
 int mggcn_csr_transpose(int32_t n_rows, int32_t n_cols, int64_t nnz, const int32_t* rowptr,
                         const int32_t* colidx, const float* val, int32_t* rowptr_t,
                         int32_t* colidx_t, float* val_t, void* ws, size_t ws_bytes, void* stream);
+
+int mggcn_csr_transpose64(int32_t n_rows, int32_t n_cols, int64_t nnz, const int64_t* rowptr,
+                          const int32_t* colidx, const float* val, int64_t* rowptr_t,
+                          int32_t* colidx_t, float* val_t, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Graph handle: A^ in CSR, optionally A^^T in CSR, and the one-time load-balancing analysis
@@ -392,8 +398,12 @@ int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labe
  *            n_rows x row_stride-byte matrix X (dev, 16-byte aligned; row_stride a multiple of 16),
  *            eight rows in flight per lane.  idx: int32 dev; an index outside [0, n_rows) is read
  *            as row n_rows - 1.
+ *   _mfma:   512 workgroups issue `iters` x 32 v_mfma_f32_32x32x2_f32 per wavefront on register
+ *            operands; returns the number of floating-point operations enqueued (or a negative
+ *            status), for the caller to divide by the time it measures.
  * ---------------------------------------------------------------------------------------- */
 int32_t mggcn_probe_sink_floats(void);
+int64_t mggcn_probe_mfma(int32_t iters, float* sink /*dev*/, void* stream);
 int mggcn_probe_read(const void* buf /*dev*/, int64_t bytes, float* sink /*dev*/, void* stream);
 int mggcn_probe_gather(const void* X /*dev*/, int64_t n_rows, int32_t row_bytes, int64_t row_stride,
                        const int32_t* idx /*dev*/, int64_t n_idx, float* sink /*dev*/, void* stream);

@@ -82,16 +82,18 @@ def mggcn_csr_normalize(n_rows, n_cols, rowptr_in, colidx_in, mode=NORM_SYM_SELF
 
 
 def mggcn_csr_transpose(n_rows, n_cols, rowptr, colidx, val, stream=None):
+    """-> (rowptr_t, colidx_t, val_t); an int64 rowptr selects the 64-bit entry point"""
     torch = _torch()
     L = B.lib()
     dev = rowptr.device
     nnz = int(colidx.numel())
     nbytes = L.mggcn_csr_transpose_workspace_bytes(n_rows, n_cols, nnz)
     ws = _ws(nbytes, dev)
-    rowptr_t = torch.empty(n_cols + 1, dtype=torch.int32, device=dev)
+    rowptr_t = torch.empty(n_cols + 1, dtype=rowptr.dtype, device=dev)
     colidx_t = torch.empty(nnz, dtype=torch.int32, device=dev)
     val_t = torch.empty(nnz, dtype=torch.float32, device=dev)
-    B.check(L.mggcn_csr_transpose(n_rows, n_cols, nnz, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rowptr_t),
+    fn = L.mggcn_csr_transpose64 if rowptr.dtype == torch.int64 else L.mggcn_csr_transpose
+    B.check(fn(n_rows, n_cols, nnz, B.ptr(rowptr), B.ptr(colidx), B.ptr(val), B.ptr(rowptr_t),
                                   B.ptr(colidx_t), B.ptr(val_t), _ws_ptr(ws), nbytes, _stream(stream)))
     _sync(stream)
     return rowptr_t, colidx_t, val_t
@@ -391,6 +393,11 @@ def mggcn_probe_read(buf, sink=None, stream=None):
         sink = torch.empty(B.lib().mggcn_probe_sink_floats(), dtype=torch.float32, device=buf.device)
     B.check(B.lib().mggcn_probe_read(B.ptr(buf), buf.numel() * buf.element_size(), B.ptr(sink), _stream(stream)))
     return sink
+
+
+def mggcn_probe_mfma(iters, sink, stream=None) -> int:
+    """Enqueue the fp32 matrix-instruction probe; -> floating-point operations it performs."""
+    return B.check(B.lib().mggcn_probe_mfma(int(iters), B.ptr(sink), _stream(stream)))
 
 
 def mggcn_probe_gather(X, idx, row_bytes=None, sink=None, stream=None):

@@ -33,6 +33,7 @@ SIGNATURES = {
     "mggcn_csr_normalize64": (C.c_int, [_i32, _i32, _vp, _vp, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mggcn_csr_transpose_workspace_bytes": (_sz, [_i32, _i32, _i64]),
     "mggcn_csr_transpose": (C.c_int, [_i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "mggcn_csr_transpose64": (C.c_int, [_i32, _i32, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "mggcn_graph_create": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(_vp)]),
     "mggcn_graph_create64": (C.c_int, [_i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, C.POINTER(_vp)]),
     "mggcn_graph_workspace_bytes": (_sz, [_vp, _i32]),
@@ -67,6 +68,7 @@ SIGNATURES = {
                                   C.c_int, _vp]),
     "mggcn_probe_sink_floats": (_i32, []),
     "mggcn_probe_read": (C.c_int, [_vp, _i64, _vp, _vp]),
+    "mggcn_probe_mfma": (_i64, [_i32, _vp, _vp]),
     "mggcn_probe_gather": (C.c_int, [_vp, _i64, _i32, _i64, _vp, _i64, _vp, _vp]),
     "mggcn_epoch": (C.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),
 }

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
@@ -78,6 +79,13 @@ size_t scan_tmp_ints(int64_t n);
 int exclusive_scan_i32(const int32_t* counts, int64_t n, int32_t* out, int32_t* tmp, hipStream_t s);
 // The same with 64-bit offsets (totals beyond 2^31); tmp needs scan_tmp_ints(n) int64 entries.
 int exclusive_scan_i64(const int32_t* counts, int64_t n, int64_t* out, int64_t* tmp, hipStream_t s);
+
+// Stable radix sort of n (key, value) pairs of 32 unsigned bits by the low key_bits bits of the key
+// (sort.hip).  vals_in == nullptr sorts the positions 0..n-1 (an argsort).  keys_in / vals_in are not
+// written; tmp needs radix_sort_tmp_bytes(n) bytes, 256-byte aligned.  n < 2^32.
+size_t radix_sort_tmp_bytes(int64_t n);
+int radix_sort_pairs(const uint32_t* keys_in, const uint32_t* vals_in, uint32_t* keys_out, uint32_t* vals_out,
+                     int64_t n, int key_bits, void* tmp, hipStream_t s);
 
 // The GeMM behind mggcn_gemm (pieces = false) and mggcn_gemm_bf16x3 (pieces = true).
 int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, const float* A, int64_t lda,

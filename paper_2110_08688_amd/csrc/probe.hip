@@ -9,7 +9,8 @@
 //                 gathers (Eq. 6, 9) with the arithmetic, the value stream and the output removed.
 //
 // Both keep a running sum per lane and store one number per workgroup, so the loads cannot be
-// dropped and the stores are negligible.
+// dropped and the stores are negligible.  A third probe issues nothing but the fp32 matrix
+// instruction of the GeMM (Eq. 5, 10, 11) on register operands.
 #include "common.h"
 
 #include <algorithm>
@@ -80,6 +81,35 @@ __global__ __launch_bounds__(kThreads) void probe_gather_kernel(const char* __re
   if (threadIdx.x == 0) sink[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
 }
 
+// Sustained issue rate of the fp32 matrix instruction the GeMM is built on, operands in registers,
+// nothing else going on: 32 independent-enough instructions (four accumulators) per loop trip.
+typedef float probe_acc __attribute__((ext_vector_type(16)));
+constexpr int kMfmaProbeBlocks = 512;  // two workgroups per CU: two wavefronts per SIMD
+__global__ __launch_bounds__(kThreads) void probe_mfma_kernel(int iters, float* __restrict__ sink) {
+  probe_acc acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  const float a = 1.f + (float)(threadIdx.x & 7) * 0.125f, b = 1.f - (float)(threadIdx.x & 3) * 0.25f;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < 4; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += acc[j][r];
+  for (int d = 1; d < 64; d <<= 1) s += __shfl_xor(s, d);
+  __shared__ float part[kThreads / 64];
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
+  __syncthreads();
+  if (threadIdx.x == 0) sink[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
 }  // namespace
 }  // namespace mggcn
 
@@ -99,6 +129,20 @@ int mggcn_probe_read(const void* buf, int64_t bytes, float* sink, void* stream) 
   probe_read_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(static_cast<const vec4*>(buf), n_vec, sink);
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
+}
+
+int64_t mggcn_probe_mfma(int32_t iters, float* sink, void* stream) {
+  if (iters < 1 || iters > (1 << 24) || !sink) {
+    fail(MGGCN_E_INVALID_ARG, "iters %d outside [1, 2^24] or sink is NULL", iters);
+    return MGGCN_E_INVALID_ARG;
+  }
+  probe_mfma_kernel<<<kMfmaProbeBlocks, kThreads, 0, as_stream(stream)>>>(iters, sink);
+  if (hipGetLastError() != hipSuccess) {
+    fail(MGGCN_E_HIP, "probe launch failed");
+    return MGGCN_E_HIP;
+  }
+  // workgroups x wavefronts x trips x instructions x (2 x 32 x 32 x 2 flop)
+  return (int64_t)kMfmaProbeBlocks * (kThreads / 64) * (int64_t)iters * 32 * 4096;
 }
 
 int mggcn_probe_gather(const void* X, int64_t n_rows, int32_t row_bytes, int64_t row_stride, const int32_t* idx,

@@ -191,6 +191,30 @@ def test_csr_transpose_exact(mg, dev, ref, shape):
     assert np.array_equal(g[2].cpu().numpy(), vat.astype(np.float32))
 
 
+def test_csr_transpose_many_tiles_passes_and_a_hub_column(mg, dev, ref):
+    """The counting sort behind the transpose at sizes that span many sort tiles with a ragged last one,
+    column counts that need two, three and four 8-bit passes, a column that every row holds (its run of
+    equal keys crosses hundreds of tiles: stability keeps the rows ascending) and empty columns."""
+    rng = np.random.default_rng(3)
+    for n, m, per_row in ((40_000, 200, 6), (9_001, 70_000, 40), (3_000, 20_000_000, 25)):
+        say(f"[transpose big] {n} x {m}, ~{per_row} per row")
+        rows = []
+        rp = np.zeros(n + 1, np.int64)
+        for i in range(n):
+            c = np.unique(np.concatenate([rng.integers(0, m, per_row), [7]]))  # column 7 in every row
+            rows.append(c)
+            rp[i + 1] = rp[i] + len(c)
+        ci = np.concatenate(rows).astype(np.int32)
+        rp = rp.astype(np.int32)
+        va = wl.normal_f32(11, n, (len(ci),))
+        rpt, cit, vat = ref.csr_transpose(n, m, rp, ci, va.astype(np.float64))
+        g = mg.mggcn_csr_transpose(n, m, to_dev(rp, dev), to_dev(ci, dev), to_dev(va, dev))
+        assert np.array_equal(g[0].cpu().numpy(), rpt) and np.array_equal(g[1].cpu().numpy(), cit)
+        assert np.array_equal(g[2].cpu().numpy(), vat.astype(np.float32))
+        g2 = mg.mggcn_csr_transpose(n, m, to_dev(rp, dev), to_dev(ci, dev), to_dev(va, dev))
+        assert all(np.array_equal(a.cpu().numpy(), b.cpu().numpy()) for a, b in zip(g, g2))
+
+
 # ----------------------------------------------------------------------------------------------
 # a2 / a6: SpMM
 # ----------------------------------------------------------------------------------------------

@@ -76,7 +76,13 @@ def test_wide_offsets_give_the_same_bits(mg, dev, ref, name, mode):
     assert np.array_equal(rp64.cpu().numpy(), rp.astype(np.int64)) and np.array_equal(ci64.cpu().numpy(), ci)
     assert np.array_equal(v64.cpu().numpy().view(np.int32), val.astype(np.float32).view(np.int32))
     t32 = mg.mggcn_csr_transpose(nr, nc, rp32, ci32, v32)
-    t64 = (t32[0].to(torch.int64), t32[1], t32[2])
+    t64 = mg.mggcn_csr_transpose(nr, nc, rp64, ci64, v64)  # the 64-bit entry point
+    assert t64[0].dtype == torch.int64
+    assert torch.equal(t64[0], t32[0].to(torch.int64)) and torch.equal(t64[1], t32[1])
+    assert torch.equal(t64[2].view(torch.int32), t32[2].view(torch.int32))
+    rpt, cit, vt = ref.csr_transpose(nr, nc, rp, ci, val.astype(np.float32).astype(np.float64))
+    assert np.array_equal(t32[0].cpu().numpy(), rpt) and np.array_equal(t32[1].cpu().numpy(), cit)
+    assert np.array_equal(t32[2].cpu().numpy(), vt.astype(np.float32))
     F = 41
     for P, seg in [(0, 0), (1, 16), (7, 0)]:
         G32 = mg.Graph(nr, nc, rp32, ci32, v32, transpose=t32, F_max=F, n_panels=P, seg_len=seg)
