@@ -98,7 +98,7 @@ def sha256_arrays(*arrays) -> str:
 
 def calibrate(mg, torch, dev, gib=8, reps=5):
     """What this machine delivers for the access patterns of the SpMM, measured in this run: a plain device
-    copy, a read-only stream, and random row gathers (512-byte and 1-KiB rows, uniform over a buffer
+    copy, a read-only and a write-only stream, and random row gathers (512-byte and 1-KiB rows, uniform over a buffer
     no cache holds)."""
     n = gib << 28  # floats
     buf = torch.empty(n, dtype=torch.float32, device=dev).fill_(1.0)
@@ -108,6 +108,8 @@ def calibrate(mg, torch, dev, gib=8, reps=5):
     out["device_copy_GBps"] = round(2.0 * half * 4 / (ms * 1e-3) / 1e9, 1)
     ms = timed(torch, lambda: mg.mggcn_probe_read(buf), reps)["min"]
     out["read_stream_GBps"] = round(n * 4 / (ms * 1e-3) / 1e9, 1)
+    ms = timed(torch, lambda: mg.mggcn_probe_write(buf, 1.0), reps)["min"]
+    out["write_stream_GBps"] = round(n * 4 / (ms * 1e-3) / 1e9, 1)
     gen = torch.Generator(device=dev).manual_seed(12345)
     for row_bytes in (512, 1024):
         X = buf.view(-1, row_bytes // 4)

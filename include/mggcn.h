@@ -394,6 +394,7 @@ int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labe
  * the SpMM's two access patterns, beside the datasheet bandwidth.
  * `sink` (dev) receives one fp32 per workgroup: room for mggcn_probe_sink_floats() entries.
  *   _read:   reads `bytes` (a multiple of 16) from buf (dev, 16-byte aligned) once, contiguously.
+ *   _write:  fills `bytes` (a multiple of 16) of buf (dev, 16-byte aligned) with `value`, contiguously.
  *   _gather: for k in [0, n_idx): reads row idx[k] (row_bytes = 64 .. 1024, a power of two) of the
  *            n_rows x row_stride-byte matrix X (dev, 16-byte aligned; row_stride a multiple of 16),
  *            eight rows in flight per lane.  idx: int32 dev; an index outside [0, n_rows) is read
@@ -403,6 +404,7 @@ int mggcn_epoch(mggcn_model* m, const float* X, int64_t ldx, const int32_t* labe
  *            status), for the caller to divide by the time it measures.
  * ---------------------------------------------------------------------------------------- */
 int32_t mggcn_probe_sink_floats(void);
+int mggcn_probe_write(void* buf /*dev*/, int64_t bytes, float value, void* stream);
 int64_t mggcn_probe_mfma(int32_t iters, float* sink /*dev*/, void* stream);
 int mggcn_probe_read(const void* buf /*dev*/, int64_t bytes, float* sink /*dev*/, void* stream);
 int mggcn_probe_gather(const void* X /*dev*/, int64_t n_rows, int32_t row_bytes, int64_t row_stride,

@@ -395,6 +395,12 @@ def mggcn_probe_read(buf, sink=None, stream=None):
     return sink
 
 
+def mggcn_probe_write(buf, value=0.0, stream=None):
+    """Fill a device tensor once, contiguously (timed by the caller)."""
+    B.check(B.lib().mggcn_probe_write(B.ptr(buf), buf.numel() * buf.element_size(), float(value), _stream(stream)))
+    return buf
+
+
 def mggcn_probe_mfma(iters, sink, stream=None) -> int:
     """Enqueue the fp32 matrix-instruction probe; -> floating-point operations it performs."""
     return B.check(B.lib().mggcn_probe_mfma(int(iters), B.ptr(sink), _stream(stream)))

@@ -68,6 +68,7 @@ SIGNATURES = {
                                   C.c_int, _vp]),
     "mggcn_probe_sink_floats": (_i32, []),
     "mggcn_probe_read": (C.c_int, [_vp, _i64, _vp, _vp]),
+    "mggcn_probe_write": (C.c_int, [_vp, _i64, _f32, _vp]),
     "mggcn_probe_mfma": (_i64, [_i32, _vp, _vp]),
     "mggcn_probe_gather": (C.c_int, [_vp, _i64, _i32, _i64, _vp, _i64, _vp, _vp]),
     "mggcn_epoch": (C.c_int, [_vp, _vp, _i64, _vp, _vp, _vp, _vp, _vp]),

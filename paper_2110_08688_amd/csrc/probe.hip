@@ -2,7 +2,8 @@
 // measured by the benchmark in the same run as the SpMM itself and quoted next to the datasheet
 // bandwidth.  Not part of the training path.
 //
-//   read stream : every workgroup reads a contiguous share of a buffer with 16-byte loads -- the
+//   read / write stream : every workgroup reads (fills) a contiguous share of a buffer with 16-byte
+//                 loads (stores) -- the
 //                 pattern of the column-index / value streams and of any dense pass over a matrix.
 //   row gather  : rows of a dense matrix are fetched in the order an index list gives, LPR lanes x
 //                 16 bytes per row, eight rows in flight per lane -- the pattern of the SpMM's
@@ -47,6 +48,15 @@ __global__ __launch_bounds__(kThreads) void probe_read_kernel(const vec4* __rest
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = s;
   __syncthreads();
   if (threadIdx.x == 0) sink[blockIdx.x] = part[0] + part[1] + part[2] + part[3];
+}
+
+// write stream: every workgroup fills a contiguous share with 16-byte stores
+__global__ __launch_bounds__(kThreads) void probe_write_kernel(vec4* __restrict__ buf, int64_t n_vec, float value) {
+  const int64_t per_block = (n_vec + gridDim.x - 1) / gridDim.x;
+  const int64_t begin = (int64_t)blockIdx.x * per_block;
+  const int64_t end = min(n_vec, begin + per_block);
+  const vec4 v = {value, value, value, value};
+  for (int64_t i = begin + threadIdx.x; i < end; i += kThreads) buf[i] = v;
 }
 
 template <int LPR>
@@ -127,6 +137,18 @@ int mggcn_probe_read(const void* buf, int64_t bytes, float* sink, void* stream) 
   const int64_t n_vec = bytes / 16;
   const int blocks = (int)std::min<int64_t>(kProbeBlocks, ceil_div(n_vec, kThreads));
   probe_read_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(static_cast<const vec4*>(buf), n_vec, sink);
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
+int mggcn_probe_write(void* buf, int64_t bytes, float value, void* stream) {
+  MGGCN_REQUIRE(bytes >= 0 && bytes % 16 == 0, MGGCN_E_INVALID_ARG, "bytes = %lld must be a non-negative multiple of 16",
+                (long long)bytes);
+  if (bytes == 0) return MGGCN_OK;
+  MGGCN_REQUIRE(buf && aligned(buf, 16), MGGCN_E_INVALID_ARG, "buf is NULL or not 16-byte aligned");
+  const int64_t n_vec = bytes / 16;
+  const int blocks = (int)std::min<int64_t>(kProbeBlocks, ceil_div(n_vec, kThreads));
+  probe_write_kernel<<<blocks, kThreads, 0, as_stream(stream)>>>(static_cast<vec4*>(buf), n_vec, value);
   MGGCN_LAUNCH_CHECK();
   return MGGCN_OK;
 }
