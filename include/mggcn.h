@@ -198,6 +198,18 @@ int mggcn_graph_destroy(mggcn_graph* g);
  *   lanes = narrower feature chunks, dealt to workgroups round-robin); 0 = leave as it is,
  *   -1 = back to the default (as many as the row needs). */
 int mggcn_graph_tune(mggcn_graph* g, int32_t panel_mib, int32_t chunk_lanes);
+/* The segment tables of a bound handle, for tests and tools (read-only; the layout may change with the
+ * library version).  form 0 = the single-pass table, 1.. = the column-panel tables in ascending panel
+ * count; returns the number of panel tables (>= 0) or a negative status.  Any output pointer may be
+ * NULL.  tasks (dev): n_tasks records {int32 row; uint32 first entry; uint32 length | first << 30 |
+ * last << 29; int32 slot (< 0: the row's result goes to Y)}, panel-major, inside a panel longest
+ * first and in row order among equal lengths; task_begin / fix_begin (host): n_panels + 1 offsets, so
+ * give room for 65 entries; fix (dev): n_fix records {int32 row, first slot, slot count; uint32 flags}
+ * of the (row, panel) ranges that were cut into several segments. */
+int mggcn_graph_tables(const mggcn_graph* g, int op /*mggcn_op*/, int32_t form, int32_t* n_panels,
+                       int64_t* n_tasks, const void** tasks /*dev*/, int64_t* task_begin /*host*/,
+                       int64_t* n_fix, const void** fix /*dev*/, int64_t* fix_begin /*host*/,
+                       int64_t* n_slots);
 /* Number of passes over the entries a plain (epilogue NONE or RELU) fp32 SpMM of width F with
  * the given op makes on this graph: column panels x feature slices (1 = single pass), or a
  * negative status. */

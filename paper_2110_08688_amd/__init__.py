@@ -135,6 +135,29 @@ class Graph:
     def tune(self, panel_mib=0, chunk_lanes=0):
         B.check(B.lib().mggcn_graph_tune(self.handle, int(panel_mib), int(chunk_lanes)))
 
+    def tables(self, op=OP_N, form=0):
+        """Segment tables of the handle as host arrays (tests): dict with n_panels, tasks (n x 4 int32 view of the
+        records: row, first entry, length | flags, slot), task_begin, fix (n x 4 int32), fix_begin, n_slots, n_forms."""
+        torch = _torch()
+        n_panels, n_tasks, n_fix, n_slots = C.c_int32(0), C.c_int64(0), C.c_int64(0), C.c_int64(0)
+        tp, fp = C.c_void_p(None), C.c_void_p(None)
+        tb, fb = (C.c_int64 * 65)(), (C.c_int64 * 65)()
+        n_forms = B.check(B.lib().mggcn_graph_tables(self.handle, op, form, C.byref(n_panels), C.byref(n_tasks), C.byref(tp), tb,
+                                                     C.byref(n_fix), C.byref(fp), fb, C.byref(n_slots)))
+        torch.cuda.synchronize()
+
+        def grab(ptr, n):
+            if n == 0:
+                return torch.zeros((0, 4), dtype=torch.int32)
+            base = _ws_ptr(self.ws)
+            off = (ptr - base) // 4
+            flat = self.ws[(base - self.ws.data_ptr()):].view(torch.int32)
+            return flat[off: off + 4 * n].view(n, 4).cpu()
+
+        P = n_panels.value
+        return dict(n_panels=P, tasks=grab(tp.value, n_tasks.value), task_begin=list(tb[: P + 1]),
+                    fix=grab(fp.value, n_fix.value), fix_begin=list(fb[: P + 1]), n_slots=n_slots.value, n_forms=n_forms)
+
     def panels(self, F, op=OP_N) -> int:
         return B.check(B.lib().mggcn_graph_panels(self.handle, op, F))
 

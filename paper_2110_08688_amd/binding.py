@@ -41,6 +41,8 @@ SIGNATURES = {
     "mggcn_graph_destroy": (C.c_int, [_vp]),
     "mggcn_graph_panels": (C.c_int, [_vp, C.c_int, _i32]),
     "mggcn_graph_tune": (C.c_int, [_vp, _i32, _i32]),
+    "mggcn_graph_tables": (C.c_int, [_vp, C.c_int, _i32, C.POINTER(_i32), C.POINTER(_i64), C.POINTER(_vp), C.POINTER(_i64),
+                                     C.POINTER(_i64), C.POINTER(_vp), C.POINTER(_i64), C.POINTER(_i64)]),
     "mggcn_spmm": (C.c_int, [_vp, C.c_int, _vp, _i64, _i32, _f32, C.c_int, _vp, _i64, _vp]),
     "mggcn_spmm_bf16": (C.c_int, [_vp, C.c_int, _vp, _i64, _i32, _f32, C.c_int, _vp, _i64, _vp]),
     "mggcn_f32_to_bf16": (C.c_int, [_i64, _i32, _vp, _i64, _vp, _i64, _vp]),

@@ -551,6 +551,29 @@ int mggcn_graph_destroy(mggcn_graph* g) {
   return MGGCN_OK;
 }
 
+int mggcn_graph_tables(const mggcn_graph* g, int op, int32_t form, int32_t* n_panels, int64_t* n_tasks,
+                       const void** tasks, int64_t* task_begin, int64_t* n_fix, const void** fix, int64_t* fix_begin,
+                       int64_t* n_slots) {
+  MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
+  MGGCN_REQUIRE(op == MGGCN_OP_N || op == MGGCN_OP_T, MGGCN_E_INVALID_ARG, "unknown op %d", op);
+  MGGCN_REQUIRE(g->bound, MGGCN_E_WORKSPACE, "graph is not bound to a workspace");
+  const Orientation& o = (op == MGGCN_OP_N || g->symmetric) ? g->fwd : g->bwd;
+  MGGCN_REQUIRE(form >= 0 && form <= (int32_t)o.panelled.size(), MGGCN_E_INVALID_ARG, "form %d outside [0, %d]", form,
+                (int)o.panelled.size());
+  const TaskSet& ts = form == 0 ? o.flat : o.panelled[(size_t)form - 1];
+  if (n_panels) *n_panels = ts.n_panels;
+  if (n_tasks) *n_tasks = ts.task_begin[(size_t)ts.n_panels];
+  if (tasks) *tasks = ts.d_tasks;
+  if (n_fix) *n_fix = ts.fix_begin[(size_t)ts.n_panels];
+  if (fix) *fix = ts.d_fix;
+  if (n_slots) *n_slots = ts.n_slots;
+  for (int32_t p = 0; p <= ts.n_panels; ++p) {
+    if (task_begin) task_begin[p] = ts.task_begin[(size_t)p];
+    if (fix_begin) fix_begin[p] = ts.fix_begin[(size_t)p];
+  }
+  return (int)o.panelled.size();
+}
+
 int mggcn_graph_tune(mggcn_graph* g, int32_t panel_mib, int32_t chunk_lanes) {
   MGGCN_REQUIRE(g != nullptr, MGGCN_E_INVALID_ARG, "graph is NULL");
   MGGCN_REQUIRE(panel_mib >= 0 && panel_mib <= (1 << 20), MGGCN_E_INVALID_ARG, "panel_mib %d outside [0, 2^20]",

@@ -936,3 +936,91 @@ def test_spmm_random_cases(mg, dev, ref):
         # forward error bound of the row sums (random sparse values cancel, so compare against |A||X|)
         assert np.all(err <= 1e-5 * np.maximum(scale.max(axis=1, keepdims=True), 1e-30)), f"case {case}: {err.max()}"
         assert np.array_equal(got[:, F:], Y0[:, F:])
+
+
+# ----------------------------------------------------------------------------------------------
+# the SpMM's segment tables against their definition written out in numpy
+# ----------------------------------------------------------------------------------------------
+
+def expected_tables(rp, ci, n_cols, P, seg_len):
+    """Row segments by the rule the header states: every row is cut at the P equal column-panel boundaries,
+    every non-empty (row, panel) range (an empty row: one empty range in panel 0) into pieces of at most seg_len
+    entries of equal size; panel-major, longest first, row order (then piece order) among equal lengths."""
+    FIRST, LAST = 1 << 30, 1 << 29
+    n = len(rp) - 1
+    width = -(-max(n_cols, 1) // P)
+    tasks = [[] for _ in range(P)]
+    fix = [[] for _ in range(P)]
+    slots = [0] * P
+    for i in range(n):
+        cols = ci[rp[i]:rp[i + 1]]
+        cut = [int(rp[i])] + [int(rp[i] + np.searchsorted(cols, min((c + 1) * width, n_cols), side="left")) for c in range(P - 1)] \
+            + [int(rp[i + 1])]
+        ne = [p for p in range(P) if cut[p + 1] > cut[p]]
+        first, last = (ne[0], ne[-1]) if ne else (0, 0)
+        for p in range(first, last + 1):
+            lo, ln = cut[p], cut[p + 1] - cut[p]
+            if ln == 0 and not (p == first and first == last):
+                continue
+            flags = (FIRST if p == first else 0) | (LAST if p == last else 0)
+            if ln <= seg_len:
+                tasks[p].append((i, lo, ln, flags, -1))
+            else:
+                nseg = -(-ln // seg_len)
+                piece = -(-ln // nseg)
+                fix[p].append((i, slots[p], nseg, flags))
+                for s in range(nseg):
+                    k0 = lo + s * piece
+                    k1 = min(lo + ln, k0 + piece)
+                    tasks[p].append((i, k0, k1 - k0, 0, slots[p]))
+                    slots[p] += 1
+    out_t, out_f, tb, fb = [], [], [0], [0]
+    for p in range(P):
+        order = sorted(range(len(tasks[p])), key=lambda k: -tasks[p][k][2])  # stable: generation order inside a length
+        out_t += [tasks[p][k] for k in order]
+        out_f += fix[p]
+        tb.append(len(out_t))
+        fb.append(len(out_f))
+    return out_t, tb, out_f, fb, max(slots)
+
+
+@pytest.mark.parametrize("name", ["adversarial", "powerlaw", "rect"])
+def test_segment_tables_match_their_definition(mg, dev, ref, name):
+    if name == "adversarial":
+        g = adversarial_pattern()
+    elif name == "powerlaw":
+        g = wl.chung_lu(1500, 90e3, 2.1, 900.0, 5)
+    else:
+        g = wl.row_block(400, 3000, 5000, 2.5, 200.0, 1.6, 3)
+    nr, nc = g.n_rows, g.n_cols
+    kw = {}
+    if nr != nc:
+        kw = dict(deg_row=np.full(nr, 3.0), deg_col=np.full(nc, 2.0))
+    rp, ci, val = ref.csr_normalize(nr, nc, g.rowptr, g.colidx, **kw)
+    v32 = val.astype(np.float32)
+    d = [to_dev(a, dev) for a in (rp, ci, v32)]
+    rpt, cit, vt = ref.csr_transpose(nr, nc, rp, ci, v32.astype(np.float64))
+    t = [to_dev(a, dev) for a in (rpt, cit, vt.astype(np.float32))]
+    for P, seg in ((0, 0), (1, 8), (5, 16), (64, 0), (3, 40)):
+        say(f"[tables] {name} n_panels={P} seg_len={seg}")
+        G = mg.Graph(nr, nc, *d, transpose=tuple(t), F_max=8, n_panels=P, seg_len=seg)
+        S = seg if seg else 2048
+        for op, (a_rp, a_ci, a_nc) in ((mg.OP_N, (rp, ci, nc)), (mg.OP_T, (rpt, cit, nr))):
+            form = 0
+            while True:
+                tab = G.tables(op, form)
+                want_t, tb, want_f, fb, n_slots = expected_tables(a_rp, a_ci, a_nc, tab["n_panels"], S)
+                got = tab["tasks"].numpy()
+                assert tab["task_begin"] == tb and tab["fix_begin"] == fb, (form, tab["task_begin"], tb)
+                exp = np.array([(r, k0, ln | fl, sl) for r, k0, ln, fl, sl in want_t], dtype=np.int64).reshape(-1, 4)
+                assert np.array_equal(got.astype(np.int64) & 0xFFFFFFFF, exp & 0xFFFFFFFF), f"{name} P={P} op={op} form={form}"
+                expf = np.array(want_f, dtype=np.int64).reshape(-1, 4)
+                assert np.array_equal(tab["fix"].numpy().astype(np.int64) & 0xFFFFFFFF, expf & 0xFFFFFFFF)
+                assert tab["n_slots"] == n_slots
+                if form == 0:
+                    assert tab["n_panels"] == 1
+                form += 1
+                if form > tab["n_forms"]:
+                    break
+            if P > 1:
+                assert G.tables(op, 1)["n_panels"] == P
