@@ -148,10 +148,10 @@ int mggcn_csr_transpose64(int32_t n_rows, int32_t n_cols, int64_t nnz, const int
  * Graph handle: A^ in CSR, optionally A^^T in CSR, and the one-time load-balancing analysis
  * the SpMM uses (rows cut into segments of bounded length, segments ordered longest first).
  *
- * _create reads rowptr (and rowptr_t) back to the host, finds on the device where every row
- * crosses the column-panel boundaries (a few bytes per row, written to pinned host memory it
- * allocates and frees itself), SYNCHRONISES the stream, and builds the segment tables on the host.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the
- * case for the symmetric normalisation of an undirected graph); op T then runs on A^ itself.
+ * _create reads rowptr (and rowptr_t) back to the host (validation, and the sizes the workspace query
+ * needs), checks on the device that every column index lies in [0, n_cols), and SYNCHRONISES the
+ * stream.  rowptr_t == NULL declares A^ symmetric (A^^T = A^, the case for the symmetric
+ * normalisation of an undirected graph); op T then runs on A^ itself.
  * The CSR arrays are borrowed, not copied: they must outlive the handle.  _create checks that
  * rowptr starts at 0 and never decreases and that every column index lies in [0, n_cols)
  * (MGGCN_E_BAD_CSR otherwise, so that no product ever gathers outside X); ascending columns
@@ -164,8 +164,10 @@ int mggcn_csr_transpose64(int32_t n_rows, int32_t n_cols, int64_t nnz, const int
  * one panel of its gathered operand down to about 12 MiB (16 MiB for a bfloat16 operand), or
  * none for a small operand;
  * 1 = never; > 1 = always that many).
- * _bind uploads the tables into caller memory of _workspace_bytes(g, F_max) bytes, which
- * also holds the partial sums of rows that were cut, for feature widths up to F_max.
+ * _bind builds the segment tables on the device (count, prefix sums, a stable sort by panel and
+ * length, fill -- a few launches per table) in caller memory of _workspace_bytes(g, F_max) bytes, which
+ * also holds the partial sums of rows that were cut, for feature widths up to F_max, and the scratch
+ * of that construction; it SYNCHRONISES the stream.
  * A handle may be re-bound; it must be bound before mggcn_spmm is called.  Products on one handle
  * share its partial-sum table: enqueue them on one stream (or otherwise keep them from
  * overlapping in time); use one handle per stream for concurrent products.

@@ -2,6 +2,8 @@
 // the operator is not symmetric) plus the row-segment tables the SpMM kernels walk.
 #pragma once
 
+#include <hip/hip_runtime.h>
+
 #include <array>
 #include <cstdint>
 #include <vector>
@@ -32,10 +34,11 @@ constexpr int kLenClasses = 7;  // length thresholds 8 << i, i = 0..6
 // in the p-th equal slice of the column range).  One panel = the classic row split.
 struct TaskSet {
   int32_t n_panels = 0;  // 0: not built
-  std::vector<Task> tasks;          // panel-major; inside a panel longest first
-  std::vector<int64_t> task_begin;  // n_panels + 1 offsets into tasks
-  std::vector<FixRow> fix;
-  std::vector<int64_t> fix_begin;   // n_panels + 1 offsets into fix
+  // upper bounds from the row lengths alone (known when the handle is created: they size the workspace)
+  int64_t max_tasks = 0, max_fix = 0, max_slots = 0;
+  // exact figures, known once the tables have been built on the device (mggcn_graph_bind)
+  std::vector<int64_t> task_begin;  // n_panels + 1 offsets into the task list (panel-major; inside a panel longest first)
+  std::vector<int64_t> fix_begin;   // n_panels + 1 offsets into the fix-up records
   std::vector<std::array<int64_t, kLenClasses>> cnt_ge;  // per panel: tasks of length >= 8 << i
   int64_t n_slots = 0;              // partial-sum rows needed by the widest panel
   Task* d_tasks = nullptr;
@@ -49,11 +52,20 @@ struct Orientation {
   bool wide = false;
   const int32_t* colidx = nullptr;
   const float* val = nullptr;
+  int32_t finest = 1;  // panel count of the finest panel table (1: none); the others use every 2nd, 4th, ... boundary
   TaskSet flat;      // one panel
   // Column-panel forms: either the one panel count the caller asked for, or one per power of two
   // up to what the average row length affords; a product picks by the size of its gathered operand.
   std::vector<TaskSet> panelled;
 };
+
+// tasks.hip: the tables of one TaskSet built on the device into d_tasks / d_fix (room for max_tasks + 1 /
+// max_fix + 1 records); fills the exact figures of *ts; synchronises the stream.  cuts: per row
+// `cut_stride` entry offsets at the finest panel boundaries (device; unused for one panel).
+size_t task_build_scratch_bytes(int64_t n_rows, int32_t n_panels, int64_t max_tasks);
+template <typename IT>
+int build_task_set_device(TaskSet* ts, int64_t n_rows, const IT* rowptr, const uint32_t* cuts, int32_t cut_stride,
+                          int32_t cut_step, int32_t seg_len, Task* d_tasks, FixRow* d_fix, void* scratch, hipStream_t s);
 
 }  // namespace mggcn
 

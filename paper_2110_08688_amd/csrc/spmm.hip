@@ -1,7 +1,8 @@
 // CSR SpMM  Y = epilogue( op(A^) X + beta Y )  for gfx950 -- the product that takes most of a
 // GCN epoch (Eq. 6 forward, Eq. 9 backward of the paper).
 //
-// Work decomposition (done once per graph, the graph being fixed for all epochs):
+// Work decomposition (done once per graph, the graph being fixed for all epochs; built on the device
+// when the handle is bound to its workspace, tasks.hip):
 //   every row is cut into segments of at most seg_len entries; a segment is a task.  Tasks are
 //   ordered longest first.  A row with one segment is written straight to Y; the segments of a
 //   cut row go to a partial-sum table and a second small kernel adds them in segment order, so
@@ -44,8 +45,7 @@ constexpr int kDefaultSegLen = 2048;
 
 // Entry offset at which each row crosses each panel boundary: cuts[i * n_cuts + c] = first entry
 // of row i whose column is >= (c + 1) * width (columns are ascending inside a row).  One thread per
-// (row, boundary), a binary search each; written straight into pinned host memory, so the host
-// never needs a copy of the column indices.
+// (row, boundary), a binary search each.
 template <typename IT>
 __global__ __launch_bounds__(kSpmmThreads) void panel_cuts(int32_t n_rows, int32_t n_cols, const IT* __restrict__ rowptr,
                                                             const int32_t* __restrict__ colidx, int64_t width,
@@ -71,85 +71,73 @@ __global__ __launch_bounds__(kSpmmThreads) void check_columns(int64_t nnz, int32
   if (k < nnz && (uint32_t)colidx[k] >= (uint32_t)n_cols) *bad = 1u;  // every writer stores the same value
 }
 
-// Row-segment tables for `n_panels` column panels, in two passes over the rows: count the tasks
-// of every (panel, length), turn the counts into the positions of a longest-first counting sort,
-// then write every task to its final place (row order is kept inside a length).
-// cuts: per row `cut_stride` boundary offsets (see panel_cuts) of which every `cut_step`-th is a
-// boundary of this table's panels; unused (may be NULL) for a single panel.
-void build_task_set(TaskSet* ts, int32_t n_rows, const std::vector<int64_t>& rowptr, const uint32_t* cuts,
-                    int32_t cut_stride, int32_t cut_step, int32_t n_panels, int32_t seg_len) {
-  const int32_t P = std::max(n_panels, 1);
-  ts->n_panels = P;
-  const size_t L = (size_t)seg_len + 1;                       // lengths 0 .. seg_len
-  std::vector<int64_t> pos((size_t)P * L, 0);                 // [panel][seg_len - length]
-  std::vector<int64_t> n_fix((size_t)P, 0), slots((size_t)P, 0);
-  std::vector<int64_t> cut((size_t)P + 1);
+// Row offsets checked and table sizes bounded in one pass over the rows, on the device: every workgroup
+// writes its own sums to host-visible memory (no atomics), the host adds the few hundred of them up.
+constexpr int kMaxForms = 8;       // the single-pass table + up to seven panel tables
+constexpr int kRowCheckBlocks = 512;
+struct FormList { int32_t n; int32_t panels[kMaxForms]; };
+struct RowCheckOut {               // one per workgroup
+  int64_t first_decreasing, first_too_long;  // row index, or -1
+  int64_t tasks[kMaxForms], fix[kMaxForms], slots[kMaxForms];
+};
 
-  // calls emit(panel, k0, len, flags, slot) for every task of row i, fix(panel, nseg, flags) for every cut row
-  auto walk_row = [&](int32_t i, auto&& emit, auto&& fix) {
-    cut[0] = rowptr[i];
-    cut[(size_t)P] = rowptr[(size_t)i + 1];
-    for (int32_t p = 1; p < P; ++p) cut[p] = (int64_t)cuts[(size_t)i * cut_stride + (size_t)p * cut_step - 1];
-    int32_t first = -1, last = -1;
-    for (int32_t p = 0; p < P; ++p)
-      if (cut[(size_t)p + 1] > cut[p]) { if (first < 0) first = p; last = p; }
-    if (first < 0) first = last = 0;  // empty row: one empty task that still writes beta*Y / zeros
-    for (int32_t p = first; p <= last; ++p) {
-      const int64_t lo = cut[p];
-      const int32_t len = (int32_t)(cut[(size_t)p + 1] - lo);  // a row is shorter than 2^29 (checked by the caller)
-      if (len == 0 && !(p == first && first == last)) continue;
-      const uint32_t flags = (p == first ? kTaskFirst : 0u) | (p == last ? kTaskLast : 0u);
-      if (len <= seg_len) {
-        emit(p, lo, len, flags, -1);
-      } else {
-        const int32_t nseg = (int32_t)ceil_div(len, seg_len);
-        const int32_t piece = (int32_t)ceil_div(len, nseg);
-        fix(p, nseg, flags);
-        for (int32_t s = 0; s < nseg; ++s) {
-          const int64_t k0 = lo + (int64_t)s * piece;
-          const int64_t k1 = std::min<int64_t>(lo + len, k0 + piece);
-          emit(p, k0, (int32_t)(k1 - k0), 0u, 0);  // slot number assigned by the caller
-        }
-      }
-    }
-  };
-
-  for (int32_t i = 0; i < n_rows; ++i)
-    walk_row(i, [&](int32_t p, int64_t, int32_t len, uint32_t, int32_t) { ++pos[(size_t)p * L + (size_t)(seg_len - len)]; },
-             [&](int32_t p, int32_t nseg, uint32_t) { ++n_fix[p]; slots[p] += nseg; });
-
-  ts->task_begin.assign((size_t)P + 1, 0);
-  ts->fix_begin.assign((size_t)P + 1, 0);
-  ts->cnt_ge.assign((size_t)P, {});
-  ts->n_slots = 0;
-  int64_t run = 0;
-  for (int32_t p = 0; p < P; ++p) {
-    const int64_t base = run;
-    for (size_t l = 0; l < L; ++l) {  // l = seg_len - length: descending lengths
-      const int64_t c = pos[(size_t)p * L + l];
-      pos[(size_t)p * L + l] = run;
-      run += c;
-      const int64_t len = (int64_t)seg_len - (int64_t)l;
-      for (int k = 0; k < kLenClasses; ++k)
-        if (len >= (8 << k)) ts->cnt_ge[p][k] = run - base;  // tasks of this panel at least that long
-    }
-    ts->task_begin[(size_t)p + 1] = run;
-    ts->fix_begin[(size_t)p + 1] = ts->fix_begin[p] + n_fix[p];
-    ts->n_slots = std::max(ts->n_slots, slots[p]);
+// Upper bounds of a table's size from the row lengths alone: a row of L entries in P panels has at most
+// min(P, L) non-empty ranges (one empty range if L = 0); a range of r entries makes ceil(r / seg_len)
+// <= r / seg_len + 1 tasks, and is cut (one fix-up record, its tasks writing to slots) only if r > seg_len.
+__host__ __device__ inline void row_bounds(int64_t len, int64_t P, int32_t seg_len, int64_t* tasks, int64_t* fix, int64_t* slots) {
+  *tasks += len == 0 ? 1 : (P < len ? P : len) + len / seg_len;
+  if (len > seg_len) {
+    const int64_t most = len / ((int64_t)seg_len + 1), cut = P < most ? P : most;
+    *fix += cut;
+    *slots += len / seg_len + cut;
   }
-  ts->tasks.assign((size_t)run, Task{0, 0u, 0u, -1});
-  ts->fix.assign((size_t)ts->fix_begin[(size_t)P], FixRow{0, 0, 0, 0u});
-  std::vector<int64_t> fix_at(ts->fix_begin.begin(), ts->fix_begin.end() - 1);
-  std::fill(slots.begin(), slots.end(), 0);
-  for (int32_t i = 0; i < n_rows; ++i)
-    walk_row(i,
-             [&](int32_t p, int64_t k0, int32_t len, uint32_t flags, int32_t slot) {
-               if (slot >= 0) slot = (int32_t)slots[p]++;
-               ts->tasks[(size_t)pos[(size_t)p * L + (size_t)(seg_len - len)]++] = {i, (uint32_t)k0, (uint32_t)len | flags, slot};
-             },
-             [&](int32_t p, int32_t nseg, uint32_t flags) {
-               ts->fix[(size_t)fix_at[p]++] = {i, (int32_t)slots[p], nseg, flags};
-             });
+}
+
+template <typename IT>
+__global__ __launch_bounds__(kSpmmThreads) void check_rows(int64_t n_rows, const IT* __restrict__ rowptr, int32_t seg_len,
+                                                            FormList forms, RowCheckOut* __restrict__ out) {
+  int64_t dec = -1, big = -1, acc[3 * kMaxForms];
+#pragma unroll
+  for (int k = 0; k < 3 * kMaxForms; ++k) acc[k] = 0;
+  for (int64_t i = (int64_t)blockIdx.x * kSpmmThreads + threadIdx.x; i < n_rows; i += (int64_t)gridDim.x * kSpmmThreads) {
+    const int64_t len = (int64_t)rowptr[i + 1] - (int64_t)rowptr[i];
+    if (len < 0) { if (dec < 0) dec = i; continue; }
+    if (len > (int64_t)kTaskLenMask && big < 0) big = i;
+#pragma unroll
+    for (int f = 0; f < kMaxForms; ++f)
+      if (f < forms.n) row_bounds(len, forms.panels[f], seg_len, &acc[f], &acc[kMaxForms + f], &acc[2 * kMaxForms + f]);
+  }
+  // block reduction: sums of the bounds, smallest offending row (as unsigned, -1 is the largest)
+  __shared__ int64_t red[kSpmmThreads / 64][3 * kMaxForms + 2];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint64_t udec = (uint64_t)dec, ubig = (uint64_t)big;
+  for (int d = 1; d < 64; d <<= 1) {
+    const uint64_t a = __shfl_xor((unsigned long long)udec, d), b = __shfl_xor((unsigned long long)ubig, d);
+    udec = a < udec ? a : udec;
+    ubig = b < ubig ? b : ubig;
+#pragma unroll
+    for (int k = 0; k < 3 * kMaxForms; ++k) acc[k] += (int64_t)__shfl_xor((long long)acc[k], d);
+  }
+  if (lane == 0) {
+    for (int k = 0; k < 3 * kMaxForms; ++k) red[wave][k] = acc[k];
+    red[wave][3 * kMaxForms] = (int64_t)udec;
+    red[wave][3 * kMaxForms + 1] = (int64_t)ubig;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    RowCheckOut o;
+    uint64_t d0 = ~0ull, b0 = ~0ull;
+    for (int k = 0; k < 3 * kMaxForms; ++k) acc[k] = 0;
+    for (int w = 0; w < kSpmmThreads / 64; ++w) {
+      for (int k = 0; k < 3 * kMaxForms; ++k) acc[k] += red[w][k];
+      d0 = (uint64_t)red[w][3 * kMaxForms] < d0 ? (uint64_t)red[w][3 * kMaxForms] : d0;
+      b0 = (uint64_t)red[w][3 * kMaxForms + 1] < b0 ? (uint64_t)red[w][3 * kMaxForms + 1] : b0;
+    }
+    o.first_decreasing = (int64_t)d0;
+    o.first_too_long = (int64_t)b0;
+    for (int f = 0; f < kMaxForms; ++f) { o.tasks[f] = acc[f]; o.fix[f] = acc[kMaxForms + f]; o.slots[f] = acc[2 * kMaxForms + f]; }
+    out[blockIdx.x] = o;
+  }
 }
 
 int pow2_floor(int64_t x) {
@@ -234,27 +222,59 @@ struct GraphCarve {
   std::vector<FixRow*> fix[2];
   float* partial;
   int64_t ldp;
+  uint32_t* cuts;                // build scratch: panel boundaries of every row of one orientation
+  void* build;                   // build scratch of one table at a time
 };
 
 size_t carve_graph(const mggcn_graph* g, int32_t F_max, void* ws, GraphCarve* out) {
   Carver c(ws);
   GraphCarve gc = {};
   int64_t slots = 0;
+  size_t cut_words = 1, build_bytes = kWsAlign;
   const Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
   for (int o = 0; o < 2; ++o) {
     if (!os[o]) continue;
     std::vector<const TaskSet*> sets = {&os[o]->flat};
     for (const TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
     for (const TaskSet* ts : sets) {
-      gc.tasks[o].push_back(c.take<Task>(ts->tasks.size() + 1));
-      gc.fix[o].push_back(c.take<FixRow>(ts->fix.size() + 1));
-      slots = std::max(slots, ts->n_slots);
+      gc.tasks[o].push_back(c.take<Task>((size_t)ts->max_tasks + 1));
+      gc.fix[o].push_back(c.take<FixRow>((size_t)ts->max_fix + 1));
+      slots = std::max(slots, ts->max_slots);
+      build_bytes = std::max(build_bytes, task_build_scratch_bytes(os[o]->n_rows, ts->n_panels, ts->max_tasks));
     }
+    if (os[o]->finest > 1) cut_words = std::max(cut_words, (size_t)os[o]->n_rows * (size_t)(os[o]->finest - 1));
   }
   gc.ldp = (int64_t)align_up((size_t)std::max(F_max, 1), 64);
   gc.partial = c.take<float>((size_t)(slots * gc.ldp) + 64);
+  // scratch of mggcn_graph_bind, free for nothing else afterwards (the tables are built once per binding)
+  gc.cuts = c.take<uint32_t>(cut_words);
+  gc.build = c.take<char>(build_bytes);
   if (out) *out = std::move(gc);
   return c.off;
+}
+
+// All tables of one orientation, built on the device into the carved workspace.
+template <typename IT>
+int build_tables(const mggcn_graph* g, Orientation* o, const GraphCarve& gc, int which, hipStream_t s) {
+  const IT* rp = static_cast<const IT*>(o->rowptr);
+  const int32_t n_cuts = o->finest - 1;
+  if (n_cuts > 0 && o->n_rows > 0) {
+    // where every row crosses the boundaries of the finest panels; coarser tables use every 2nd, 4th, ... of them
+    const int64_t width = ceil_div(std::max(o->n_cols, 1), o->finest);
+    const int64_t items = (int64_t)o->n_rows * n_cuts;
+    MGGCN_REQUIRE(ceil_div(items, kThreads) < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "panel boundary grid too large");
+    panel_cuts<IT><<<(unsigned)ceil_div(items, kThreads), kThreads, 0, s>>>(o->n_rows, o->n_cols, rp, o->colidx, width, n_cuts,
+                                                                           gc.cuts);
+    MGGCN_LAUNCH_CHECK();
+  }
+  int rc = build_task_set_device<IT>(&o->flat, o->n_rows, rp, nullptr, 0, 0, g->seg_len, gc.tasks[which][0], gc.fix[which][0],
+                                     gc.build, s);
+  for (size_t k = 0; !rc && k < o->panelled.size(); ++k) {
+    TaskSet& ts = o->panelled[k];
+    rc = build_task_set_device<IT>(&ts, o->n_rows, rp, gc.cuts, n_cuts, o->finest / ts.n_panels, g->seg_len,
+                                   gc.tasks[which][k + 1], gc.fix[which][k + 1], gc.build, s);
+  }
+  return rc;
 }
 
 }  // namespace
@@ -291,18 +311,13 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
   auto setup = [&](Orientation* o, int32_t nr, int32_t nc, const IT* rp, const int32_t* ci,
                    const float* va) -> int {
     o->n_rows = nr; o->n_cols = nc; o->rowptr = rp; o->wide = sizeof(IT) == 8; o->colidx = ci; o->val = va;
-    std::vector<IT> raw((size_t)nr + 1);
-    MGGCN_HIP(hipMemcpyAsync(raw.data(), rp, sizeof(IT) * ((size_t)nr + 1), hipMemcpyDeviceToHost, s));
+    IT ends[2] = {0, 0};  // rowptr[0], rowptr[nr]
+    MGGCN_HIP(hipMemcpyAsync(&ends[0], rp, sizeof(IT), hipMemcpyDeviceToHost, s));
+    MGGCN_HIP(hipMemcpyAsync(&ends[1], rp + nr, sizeof(IT), hipMemcpyDeviceToHost, s));
     MGGCN_HIP(hipStreamSynchronize(s));
-    std::vector<int64_t> h(raw.begin(), raw.end());
-    std::vector<IT>().swap(raw);
-    MGGCN_REQUIRE(h[0] == 0, MGGCN_E_BAD_CSR, "rowptr[0] = %lld, expected 0", (long long)h[0]);
-    for (int32_t i = 0; i < nr; ++i) {
-      MGGCN_REQUIRE(h[(size_t)i + 1] >= h[i], MGGCN_E_BAD_CSR, "rowptr decreases at row %d", i);
-      MGGCN_REQUIRE(h[(size_t)i + 1] - h[i] <= (int64_t)kTaskLenMask, MGGCN_E_OVERFLOW,
-                    "row %d holds %lld entries, a row may hold 2^29 - 1", i, (long long)(h[(size_t)i + 1] - h[i]));
-    }
-    o->nnz = h[nr];
+    MGGCN_REQUIRE(ends[0] == 0, MGGCN_E_BAD_CSR, "rowptr[0] = %lld, expected 0", (long long)ends[0]);
+    MGGCN_REQUIRE(ends[1] >= 0, MGGCN_E_BAD_CSR, "rowptr[%d] = %lld is negative", nr, (long long)ends[1]);
+    o->nnz = (int64_t)ends[1];
     MGGCN_REQUIRE(o->nnz < ((int64_t)1 << 32), MGGCN_E_OVERFLOW,
                   "%lld entries: entry offsets are held in 32 unsigned bits", (long long)o->nnz);
     MGGCN_REQUIRE(o->nnz == 0 || (ci && va), MGGCN_E_INVALID_ARG, "colidx / val is NULL");
@@ -320,27 +335,53 @@ int graph_create_impl(int32_t n_rows, int32_t n_cols, const IT* rowptr, const in
       if (e != hipSuccess) return fail(MGGCN_E_HIP, "column index check failed: %s", hipGetErrorString(e));
       MGGCN_REQUIRE(*bad.p == 0u, MGGCN_E_BAD_CSR, "a column index lies outside [0, %d)", nc);
     }
-    build_task_set(&o->flat, nr, h, nullptr, 0, 0, 1, seg_len);
+    // The tables themselves are built on the device when the handle is bound; here only their forms
+    // (one panel; n_panels panels, or 2, 4, 8, ... as far as the average row length affords, over one
+    // common finest width) and the upper bounds of their sizes, which the workspace query needs.
+    o->flat.n_panels = 1;
     const int32_t Pmax = n_panels > 0 ? n_panels : max_panels(nr, o->nnz);
+    o->finest = 1;
     if (Pmax > 1 && nr > 0) {
-      // Where every row crosses the panel boundaries is found on the device and lands in pinned
-      // host memory; the panel forms for fewer panels use every 2nd, 4th, ... of the same cuts
-      // (an automatic set has power-of-two panel counts over one common finest width).
-      const int32_t n_cuts = Pmax - 1;
-      const int64_t width = ceil_div(std::max(nc, 1), Pmax);
-      Pinned pinned;
-      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&pinned.p), sizeof(uint32_t) * (size_t)nr * (size_t)n_cuts, hipHostMallocDefault));
-      uint32_t* cuts = pinned.p;
-      const int64_t items = (int64_t)nr * n_cuts;
-      panel_cuts<IT><<<(unsigned)ceil_div(items, kThreads), kThreads, 0, s>>>(nr, nc, rp, ci, width, n_cuts, cuts);
-      hipError_t e = hipGetLastError();
-      if (e == hipSuccess) e = hipStreamSynchronize(s);
-      if (e != hipSuccess) return fail(MGGCN_E_HIP, "panel boundary search failed: %s", hipGetErrorString(e));
+      o->finest = Pmax;
       for (int32_t P = n_panels > 0 ? n_panels : 2; P <= Pmax; P *= 2) {
         o->panelled.emplace_back();
-        build_task_set(&o->panelled.back(), nr, h, cuts, n_cuts, Pmax / P, P, seg_len);
+        o->panelled.back().n_panels = P;
       }
     }
+    std::vector<TaskSet*> sets = {&o->flat};
+    for (TaskSet& t : o->panelled) sets.push_back(&t);
+    MGGCN_REQUIRE(sets.size() <= (size_t)kMaxForms, MGGCN_E_UNSUPPORTED, "%zu table forms", sets.size());
+    if (nr > 0) {
+      FormList forms = {};
+      forms.n = (int32_t)sets.size();
+      for (size_t f = 0; f < sets.size(); ++f) forms.panels[f] = sets[f]->n_panels;
+      struct PinnedOut {
+        RowCheckOut* p = nullptr;
+        ~PinnedOut() { if (p) (void)hipHostFree(p); }
+      } res;
+      MGGCN_HIP(hipHostMalloc(reinterpret_cast<void**>(&res.p), sizeof(RowCheckOut) * kRowCheckBlocks, hipHostMallocDefault));
+      const int blocks = (int)std::min<int64_t>(kRowCheckBlocks, ceil_div(nr, kThreads));
+      check_rows<IT><<<blocks, kThreads, 0, s>>>(nr, rp, seg_len, forms, res.p);
+      hipError_t e = hipGetLastError();
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+      if (e != hipSuccess) return fail(MGGCN_E_HIP, "row offset check failed: %s", hipGetErrorString(e));
+      int64_t dec = -1, big = -1;
+      for (int b = 0; b < blocks; ++b) {
+        const RowCheckOut& r = res.p[b];
+        if (r.first_decreasing >= 0 && (dec < 0 || r.first_decreasing < dec)) dec = r.first_decreasing;
+        if (r.first_too_long >= 0 && (big < 0 || r.first_too_long < big)) big = r.first_too_long;
+        for (size_t f = 0; f < sets.size(); ++f) {
+          sets[f]->max_tasks += r.tasks[f];
+          sets[f]->max_fix += r.fix[f];
+          sets[f]->max_slots += r.slots[f];
+        }
+      }
+      MGGCN_REQUIRE(dec < 0, MGGCN_E_BAD_CSR, "rowptr decreases at row %lld", (long long)dec);
+      MGGCN_REQUIRE(big < 0, MGGCN_E_OVERFLOW, "row %lld holds more than 2^29 - 1 entries", (long long)big);
+    }
+    for (TaskSet* ts : sets)
+      MGGCN_REQUIRE(ts->max_tasks < ((int64_t)1 << 32), MGGCN_E_OVERFLOW, "%lld row segments: positions are held in 32 unsigned bits",
+                    (long long)ts->max_tasks);
     return MGGCN_OK;
   };
   int rc = guarded([&] { return setup(&g->fwd, n_rows, n_cols, rowptr, colidx, val); });
@@ -523,21 +564,10 @@ int mggcn_graph_bind(mggcn_graph* g, int32_t F_max, void* ws, size_t ws_bytes, v
     Orientation* os[2] = {&g->fwd, g->symmetric ? nullptr : &g->bwd};
     for (int o = 0; o < 2; ++o) {
       if (!os[o]) continue;
-      std::vector<TaskSet*> sets = {&os[o]->flat};
-      for (TaskSet& ts : os[o]->panelled) sets.push_back(&ts);
-      for (size_t k = 0; k < sets.size(); ++k) {
-        TaskSet* ts = sets[k];
-        ts->d_tasks = gc.tasks[o][k];
-        ts->d_fix = gc.fix[o][k];
-        if (!ts->tasks.empty())
-          MGGCN_HIP(hipMemcpyAsync(ts->d_tasks, ts->tasks.data(), sizeof(Task) * ts->tasks.size(),
-                                   hipMemcpyHostToDevice, s));
-        if (!ts->fix.empty())
-          MGGCN_HIP(hipMemcpyAsync(ts->d_fix, ts->fix.data(), sizeof(FixRow) * ts->fix.size(),
-                                   hipMemcpyHostToDevice, s));
-      }
+      const int rc = os[o]->wide ? build_tables<int64_t>(g, os[o], gc, o, s) : build_tables<int32_t>(g, os[o], gc, o, s);
+      if (rc) return rc;
     }
-    MGGCN_HIP(hipStreamSynchronize(s));  // host vectors may be touched again after return
+    MGGCN_HIP(hipStreamSynchronize(s));
     g->d_partial = gc.partial;
     g->ldp = gc.ldp;
     g->F_bound = F_max;
