@@ -25,6 +25,16 @@ constexpr int kThreads = 256;
 constexpr int kXcds = 8;  // accelerator dies of an MI355X, each with its own L2
 
 typedef float float16v __attribute__((ext_vector_type(16)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+
+// Buffer descriptor over `bytes` bytes at `base` (a value every lane agrees on): untyped 32-bit
+// data, no stride.  A load through it takes its base from scalar registers and a 32-bit offset per
+// lane, and returns 0 instead of touching memory at offsets of `bytes` or more; the range field
+// has 32 bits, so longer ranges are cut to 4 GiB - 1 (a tile's own offsets stay far below that).
+__device__ inline __amdgpu_buffer_rsrc_t buffer_over(const float* base, int64_t bytes) {
+  const int64_t n = bytes < 0 ? 0 : (bytes > 0xffffffffll ? 0xffffffffll : bytes);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, (int)(uint32_t)n, 0x00020000);
+}
 
 // Tile of an operand whose memory rows run along K (A not transposed, or B transposed):
 // R rows x BK, staged as 4 consecutive k per thread.
@@ -80,6 +90,37 @@ struct KContig {
     for (int p = 0; p < kPasses; ++p)
 #pragma unroll
       for (int i = 0; i < 4; ++i) S[4 * kq + i][p * kRowsPerPass + r] = reg[p * 4 + i];
+  }
+  // The tile as it lies in memory, S[row][k]: one 16-byte store per piece.
+  template <int LD>
+  __device__ static inline void store_rows(float (*S)[LD], const float (&reg)[kRegs]) {
+    static_assert(LD % 4 == 0, "row stride must keep 16-byte alignment");
+    const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p)
+      *reinterpret_cast<float4*>(&S[p * kRowsPerPass + r][4 * kq]) =
+          make_float4(reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]);
+  }
+  // Byte offsets of this thread's 16-byte pieces from the tile's corner; they do not change along K.
+  __device__ static inline void offsets(int64_t ld, uint32_t (&off)[kPasses]) {
+    const int r = threadIdx.x / kThreadsPerRow, kq = threadIdx.x % kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) off[p] = (uint32_t)(((int64_t)(p * kRowsPerPass + r) * ld + 4 * kq) * 4);
+  }
+  // A whole k-step through the buffer path: the base is the tile's corner at column k0 (scalar
+  // registers), the hardware returns 0 for anything past the last valid byte of the matrix, so the
+  // rows of a ragged last tile need no test.  k0 + BK <= n_k.
+  __device__ static inline void load_buffer(const float* __restrict__ src, int64_t ld, int64_t row0, int64_t row_end,
+                                            int64_t k0, int64_t n_k, const uint32_t (&off)[kPasses],
+                                            float (&reg)[kRegs]) {
+    const __amdgpu_buffer_rsrc_t rs =
+        buffer_over(src + row0 * ld + k0, ((row_end - row0 - 1) * ld + (n_k - k0)) * (int64_t)sizeof(float));
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const uint4v t = __builtin_amdgcn_raw_buffer_load_b128(rs, off[p], 0, 0);
+      reg[p * 4 + 0] = __uint_as_float(t.x); reg[p * 4 + 1] = __uint_as_float(t.y);
+      reg[p * 4 + 2] = __uint_as_float(t.z); reg[p * 4 + 3] = __uint_as_float(t.w);
+    }
   }
 };
 
@@ -138,6 +179,27 @@ struct MContig {
     for (int p = 0; p < kPasses; ++p)
       *reinterpret_cast<float4*>(&S[p * kRowsPerPass + kr][4 * cq]) =
           make_float4(reg[p * 4 + 0], reg[p * 4 + 1], reg[p * 4 + 2], reg[p * 4 + 3]);
+  }
+  __device__ static inline void offsets(int64_t ld, uint32_t (&off)[kPasses]) {
+    const int cq = threadIdx.x % kThreadsPerRow, kr = threadIdx.x / kThreadsPerRow;
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) off[p] = (uint32_t)(((int64_t)(p * kRowsPerPass + kr) * ld + 4 * cq) * 4);
+  }
+  // As above; memory rows run along the tile's M/N side here, so the base moves down BK rows per
+  // k-step.  Columns past col_end of a ragged tile read the neighbouring row (finite or not, they
+  // only reach accumulators that are never stored) except in the matrix's last row, where the
+  // range check returns 0.  k0 + BK <= n_k.
+  __device__ static inline void load_buffer(const float* __restrict__ src, int64_t ld, int64_t col0, int64_t col_end,
+                                            int64_t k0, int64_t n_k, const uint32_t (&off)[kPasses],
+                                            float (&reg)[kRegs]) {
+    const __amdgpu_buffer_rsrc_t rs =
+        buffer_over(src + k0 * ld + col0, ((n_k - k0 - 1) * ld + (col_end - col0)) * (int64_t)sizeof(float));
+#pragma unroll
+    for (int p = 0; p < kPasses; ++p) {
+      const uint4v t = __builtin_amdgcn_raw_buffer_load_b128(rs, off[p], 0, 0);
+      reg[p * 4 + 0] = __uint_as_float(t.x); reg[p * 4 + 1] = __uint_as_float(t.y);
+      reg[p * 4 + 2] = __uint_as_float(t.z); reg[p * 4 + 3] = __uint_as_float(t.w);
+    }
   }
 };
 
@@ -204,6 +266,45 @@ __device__ inline void store_tiles(const float16v (&acc)[TM][TN], int64_t row0, 
         }
       }
     }
+}
+
+// The same for a wavefront whose TM x TN tiles lie wholly inside C: no test per element, and no
+// vector arithmetic for addresses -- one buffer descriptor over the wavefront's block, one offset
+// per lane, and the offset of each accumulator register's row in a scalar register.
+template <int TM, int TN>
+__device__ inline void store_whole_tiles(const float16v (&acc)[TM][TN], int64_t row0, int64_t col0, int64_t M,
+                                         int64_t N, int64_t split, float* __restrict__ C, int64_t ldc, float beta,
+                                         int epi, float* __restrict__ partial) {
+  const int lane = threadIdx.x & 63;
+  const int frow = lane >> 5, fcol = lane & 31;
+  const bool to_partial = partial != nullptr;
+  float* out = to_partial ? partial + split * M * N : C;
+  const int64_t ldo = to_partial ? N : ldc;
+  const __amdgpu_buffer_rsrc_t rs =
+      buffer_over(out + row0 * ldo + col0, ((TM * 32 - 1) * ldo + TN * 32) * (int64_t)sizeof(float));
+  const uint32_t lane_off = (uint32_t)((4 * frow * ldo + fcol) * 4);
+  // the choice is the same for every element: made once, outside the unrolled stores
+  auto sweep = [&](auto mode) {
+    constexpr int kMode = decltype(mode)::value;  // 0: as it is, 1: ReLU, 2: needs the old value of C
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const uint32_t reg_off = (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4);
+          float v = acc[i][j][r];
+          if constexpr (kMode == 1) v = v > 0.f ? v : 0.f;
+          if constexpr (kMode == 2) {
+            const float old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_off, reg_off, 0));
+            v = gemm_epilogue(v, old, beta, epi);
+          }
+          __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, lane_off, reg_off, 0);
+        }
+  };
+  if (to_partial || (beta == 0.f && epi == MGGCN_EPI_NONE)) sweep(std::integral_constant<int, 0>{});
+  else if (beta == 0.f && epi == MGGCN_EPI_RELU) sweep(std::integral_constant<int, 1>{});
+  else sweep(std::integral_constant<int, 2>{});
 }
 
 // WM x WN wavefronts tile the BM x BN block; each wavefront holds TM x TN accumulators of 32x32.
@@ -295,6 +396,207 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
   }
 
   store_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, whole, M, N, split, C, ldc, beta, epi, partial);
+}
+
+
+// The same product for the shapes that carry the time: 16-byte aligned rows and whole tiles
+// along N (the host checks both).  What differs from gemm_mfma:
+//   * operands travel global -> registers through buffer loads whose base lives in scalar
+//     registers and whose per-lane offsets are fixed for the whole tile, so that a k-step issues
+//     no vector arithmetic for addresses (vector instructions take issue slots from the matrix
+//     pipe of the same SIMD), and a ragged last row tile is handled by the range check of the
+//     descriptor instead of predicates;
+//   * two LDS stages and one barrier per k-step: the loads of step s+1 are issued before the
+//     matrix instructions of step s and written to the other stage after them;
+//   * for N a multiple of 128 the tile is 128 x 128 with 64 x 64 per wavefront: one LDS read per
+//     matrix instruction instead of 1.5 and two thirds of the global bytes per flop.  On this
+//     chip that is what decides the speed on real data: the same instruction stream runs
+//     ~20 % slower on random operands than on constant ones with 32 x 64 per wavefront (the
+//     clock is lowered under the switching activity of LDS, load path and matrix pipes
+//     together) and ~5 % slower with 64 x 64.
+// A ragged last k-step goes through the checked loaders of gemm_mfma.
+// Where a workgroup's next tile is.  Virtual workgroup ids follow decode_tile's order (unsplit: the N
+// tiles of an M tile next to each other on one XCD; ids that only pad the grid to whole groups of
+// 8 M tiles are skipped), and a workgroup takes the ids blockIdx.x, blockIdx.x + gridDim.x, ...:
+// with a grid that is a multiple of 8 it stays on its XCD's share of the tiles.
+struct TilePos {
+  uint32_t id;
+  int64_t m0, n0, kb, ke;
+  int64_t split, steps, whole_steps;
+};
+
+__device__ inline bool locate_tile(uint32_t id, uint32_t n_ids, uint32_t stride, uint32_t tiles_m, uint32_t tiles_n,
+                                   uint32_t splits, int64_t K, int64_t k_per_split, int bm, int bn, int bk,
+                                   TilePos* pos) {
+  for (; id < n_ids; id += stride) {
+    uint32_t tm, tn, split;
+    if (splits == 1) {
+      const uint32_t xcd = id % kXcds, local = id / kXcds;
+      tn = local % tiles_n;
+      tm = (local / tiles_n) * kXcds + xcd;
+      split = 0;
+      if (tm >= tiles_m) continue;
+    } else {
+      const uint32_t per = tiles_m * tiles_n, t = id % per;
+      split = id / per;
+      tm = t % tiles_m;
+      tn = t / tiles_m;
+    }
+    pos->id = id;
+    pos->m0 = (int64_t)tm * bm;
+    pos->n0 = (int64_t)tn * bn;
+    pos->split = split;
+    pos->kb = (int64_t)split * k_per_split;
+    pos->ke = min(K, pos->kb + k_per_split);
+    pos->steps = (pos->ke - pos->kb + bk - 1) / bk;
+    pos->whole_steps = (pos->ke - pos->kb) / bk;
+    return true;
+  }
+  return false;
+}
+
+template <int BN, int WM, int WN, bool TA, bool TB>
+__global__ __launch_bounds__(kThreads) void gemm_stream(int64_t M, int64_t N, int64_t K,
+                                                         const float* __restrict__ A, int64_t lda,
+                                                         const float* __restrict__ B, int64_t ldb,
+                                                         float* __restrict__ C, int64_t ldc, float beta, int epi,
+                                                         int64_t k_per_split, float* __restrict__ partial,
+                                                         uint32_t n_ids, uint32_t tiles_m, uint32_t tiles_n,
+                                                         uint32_t splits) {
+  static_assert(WM * WN == kThreads / 64, "four wavefronts");
+  constexpr int BM = 128, BK = 32, TM = BM / WM / 32, TN = BN / WN / 32;
+  // An operand whose memory rows run along K keeps that order in LDS, S[m][k] with rows of 36
+  // floats: 16-byte stores, and a fragment is one 16-byte read per four matrix instructions (16
+  // neighbouring lanes fall on 64 distinct banks).  The other kind is staged k-major, S[k][m], and
+  // read 4 bytes at a time.  Lane l of matrix instruction t of the q-th group of eight k feeds
+  // k = 8q + 4(l/32) + t for both operands, which is the order the 16-byte reads deliver.
+  constexpr bool kRowsA = !TA, kRowsB = TB;
+  constexpr int LDA = kRowsA ? BK + 4 : BM + 4;
+  constexpr int LDB = kRowsB ? BK + 4 : BN + 4;
+  using LoadA = typename std::conditional<TA, MContig<BM, BK>, KContig<BM, BK>>::type;
+  using LoadB = typename std::conditional<TB, KContig<BN, BK>, MContig<BN, BK>>::type;
+
+  __shared__ __attribute__((aligned(16))) float As[2][kRowsA ? BM : BK][LDA];
+  __shared__ __attribute__((aligned(16))) float Bs[2][kRowsB ? BN : BK][LDB];
+
+  // the wavefront's number as a scalar: what depends on it (its corner of the tile, the buffer
+  // descriptor of its part of C) then lives in scalar registers
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  TilePos cur;
+  if (!locate_tile(blockIdx.x, n_ids, gridDim.x, tiles_m, tiles_n, splits, K, k_per_split, BM, BN, BK, &cur)) return;
+
+  float16v acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  uint32_t offA[LoadA::kPasses], offB[LoadB::kPasses];
+  LoadA::offsets(lda, offA);
+  LoadB::offsets(ldb, offB);
+  float ra[LoadA::kRegs], rb[LoadB::kRegs];
+  auto load_step = [&](const TilePos& t, int64_t s) {
+    const int64_t k = t.kb + s * BK;
+    if (s < t.whole_steps) {
+      LoadA::load_buffer(A, lda, t.m0, M, k, K, offA, ra);
+      LoadB::load_buffer(B, ldb, t.n0, N, k, K, offB, rb);
+    } else {
+      LoadA::template load<false>(A, lda, t.m0, M, k, t.ke, 4, ra);
+      LoadB::template load<false>(B, ldb, t.n0, N, k, t.ke, 4, rb);
+    }
+  };
+  const int frow = lane >> 5, fcol = lane & 31;
+  auto stage_tiles = [&](int stage) {
+    if constexpr (kRowsA) LoadA::template store_rows<LDA>(As[stage], ra);
+    else LoadA::template store<LDA>(As[stage], ra);
+    if constexpr (kRowsB) LoadB::template store_rows<LDB>(Bs[stage], rb);
+    else LoadB::template store<LDB>(Bs[stage], rb);
+  };
+  auto multiply = [&](int stage) {
+    float a[BK / 2][TM], b[BK / 2][TN];
+#pragma unroll
+    for (int q = 0; q < BK / 8; ++q) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if constexpr (kRowsA) {
+          const float4 v = *reinterpret_cast<const float4*>(&As[stage][(wm * TM + i) * 32 + fcol][8 * q + 4 * frow]);
+          a[4 * q + 0][i] = v.x; a[4 * q + 1][i] = v.y; a[4 * q + 2][i] = v.z; a[4 * q + 3][i] = v.w;
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) a[4 * q + t][i] = As[stage][8 * q + 4 * frow + t][(wm * TM + i) * 32 + fcol];
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (kRowsB) {
+          const float4 v = *reinterpret_cast<const float4*>(&Bs[stage][(wn * TN + j) * 32 + fcol][8 * q + 4 * frow]);
+          b[4 * q + 0][j] = v.x; b[4 * q + 1][j] = v.y; b[4 * q + 2][j] = v.z; b[4 * q + 3][j] = v.w;
+        } else {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) b[4 * q + t][j] = Bs[stage][8 * q + 4 * frow + t][(wn * TN + j) * 32 + fcol];
+        }
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 2; ++kk)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kk][i], b[kk][j], acc[i][j], 0, 0, 0);
+    // LDS reads one group of eight k ahead of the matrix instructions that consume them
+    constexpr int kReads = (kRowsA ? TM : 4 * TM) + (kRowsB ? TN : 4 * TN);  // per group of eight k
+    __builtin_amdgcn_sched_group_barrier(0x100, kReads, 0);
+#pragma unroll
+    for (int q = 0; q < BK / 8; ++q)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        __builtin_amdgcn_sched_group_barrier(0x008, TM * TN, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (kReads + 3) / 4, 0);
+      }
+  };
+
+  load_step(cur, 0);
+  stage_tiles(0);
+  __syncthreads();
+  int stage = 0;
+  for (;;) {
+    // all k-steps of the tile but the last: the accumulators see nothing but matrix instructions
+    for (int64_t s = 0; s + 1 < cur.steps; ++s) {
+      load_step(cur, s + 1);  // in flight during the matrix instructions below
+      multiply(stage);
+      stage_tiles(stage ^ 1);
+      __syncthreads();  // the other stage is complete, and everyone is done reading this one
+      stage ^= 1;
+    }
+    // the last one: the first operands of the workgroup's next tile are on their way while this
+    // tile's result is written
+    TilePos nxt;
+    const bool more =
+        locate_tile(cur.id + gridDim.x, n_ids, gridDim.x, tiles_m, tiles_n, splits, K, k_per_split, BM, BN, BK, &nxt);
+    if (more) load_step(nxt, 0);
+    multiply(stage);
+    if (cur.m0 + BM <= M)
+      store_whole_tiles<TM, TN>(acc, cur.m0 + wm * TM * 32, cur.n0 + wn * TN * 32, M, N, cur.split, C, ldc, beta, epi,
+                                partial);
+    else
+      store_tiles<TM, TN>(acc, cur.m0 + wm * TM * 32, cur.n0 + wn * TN * 32, false, M, N, cur.split, C, ldc, beta, epi,
+                          partial);
+    if (!more) break;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    stage_tiles(stage ^ 1);
+    __syncthreads();
+    stage ^= 1;
+    cur = nxt;
+  }
 }
 
 
@@ -534,20 +836,25 @@ __global__ __launch_bounds__(kThreads) void gemm_reduce_splits(int64_t M, int64_
 
 struct Shape {
   bool pieces;  // the bfloat16-piece kernel (128 x bn tiles, k-steps of 32) instead of the fp32 one
+  bool wide;    // the fp32 kernel with 128 x 128 tiles (gemm_stream; aligned operands, N a multiple of 128)
   int bn, bk;
   int64_t tiles_m, tiles_n;
   int splits;
   int64_t k_per_split;
 };
 
+// per-lane byte offsets of a 128-row tile stay below 2^31 for rows shorter than this
+constexpr int64_t kStreamMaxLd = (int64_t)1 << 21;
 constexpr int kBM = 128, kBN = 64;  // fp32 kernel: 72 VGPRs + 32 accumulators, 4 wavefronts per SIMD
 
-// pieces: the caller asked for the bfloat16-piece kernel (it needs two k-steps of 32 to pay)
-Shape plan_shape(bool pieces, int opA, int64_t M, int64_t N, int64_t K) {
+// pieces: the caller asked for the bfloat16-piece kernel (it needs two k-steps of 32 to pay);
+// aligned: rows of both operands start on 16-byte boundaries
+Shape plan_shape(bool pieces, bool aligned, int opA, int64_t M, int64_t N, int64_t K) {
   Shape s;
   s.pieces = pieces && K >= 64;
   s.bk = (K >= 64) ? 32 : 16;
-  s.bn = s.pieces ? (N > 64 ? 128 : 64) : kBN;
+  s.wide = !s.pieces && aligned && s.bk == 32 && N % 128 == 0;
+  s.bn = s.pieces ? (N > 64 ? 128 : 64) : (s.wide ? 128 : kBN);
   const int BK = s.bk;
   s.tiles_m = ceil_div(std::max<int64_t>(M, 1), kBM);
   s.tiles_n = ceil_div(std::max<int64_t>(N, 1), s.bn);
@@ -555,9 +862,10 @@ Shape plan_shape(bool pieces, int opA, int64_t M, int64_t N, int64_t K) {
   s.k_per_split = std::max<int64_t>(align_up((size_t)std::max<int64_t>(K, 1), BK), BK);
   if (opA == MGGCN_OP_T && K > 4096) {
     const int64_t tiles = s.tiles_m * s.tiles_n;
-    // all workgroups resident at once: 256 CUs x 4, or x 2 for the piece kernel with its 60 KB of
-    // LDS (a few more would run as a second round behind the first and double the kernel's time)
-    int64_t want = std::max<int64_t>((s.pieces ? 512 : 1024) / tiles, 1);
+    // all workgroups resident at once: 256 CUs x 4, or x 2 for the kernels with 128 x 128 tiles and
+    // their 60-67 KB of LDS (a few more would run as a second round behind the first and double
+    // the kernel's time)
+    int64_t want = std::max<int64_t>((s.pieces || s.wide ? 512 : 1024) / tiles, 1);
     want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
     want = std::max<int64_t>(want, 1);
     s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
@@ -618,6 +926,27 @@ int launch_all(const GemmArgs& g, const Shape& s) {
   if (s.pieces) {
     if (s.bn == 128) fast ? launch_pieces<128, true>(g, s, grid) : launch_pieces<128, false>(g, s, grid);
     else fast ? launch_pieces<64, true>(g, s, grid) : launch_pieces<64, false>(g, s, grid);
+  } else if (s.bk == 32 && fast && g.lda < kStreamMaxLd && g.ldb < kStreamMaxLd && g.ldc < kStreamMaxLd) {
+    // as many workgroups as the chip holds at once (a multiple of 8); each walks its share of the tiles
+    const dim3 pgrid((unsigned)std::min<int64_t>(nblk, (s.wide ? 2 : 3) * 256), 1, 1);
+#define MGGCN_GEMM_LAUNCH(TA, TB)                                                                               \
+  do {                                                                                                          \
+    if (s.wide)                                                                                                 \
+      gemm_stream<128, 2, 2, TA, TB><<<pgrid, kThreads, 0, g.st>>>(g.M, g.N, g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc, \
+                                                                   g.beta, g.epi, s.k_per_split, g.partial,       \
+                                                                   (uint32_t)nblk, (uint32_t)s.tiles_m,           \
+                                                                   (uint32_t)s.tiles_n, (uint32_t)s.splits);      \
+    else                                                                                                        \
+      gemm_stream<64, 4, 1, TA, TB><<<pgrid, kThreads, 0, g.st>>>(g.M, g.N, g.K, g.A, g.lda, g.B, g.ldb, g.C, g.ldc,  \
+                                                                  g.beta, g.epi, s.k_per_split, g.partial,        \
+                                                                  (uint32_t)nblk, (uint32_t)s.tiles_m,            \
+                                                                  (uint32_t)s.tiles_n, (uint32_t)s.splits);       \
+  } while (0)
+    if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(false, false);
+    else if (g.opA == MGGCN_OP_T && g.opB == MGGCN_OP_N) MGGCN_GEMM_LAUNCH(true, false);
+    else if (g.opA == MGGCN_OP_N && g.opB == MGGCN_OP_T) MGGCN_GEMM_LAUNCH(false, true);
+    else MGGCN_GEMM_LAUNCH(true, true);
+#undef MGGCN_GEMM_LAUNCH
   } else if (s.bk == 32) {
     fast ? launch_fp32<32, true>(g, s, grid) : launch_fp32<32, false>(g, s, grid);
   } else {
@@ -649,7 +978,14 @@ int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, con
   if (M == 0 || N == 0) return MGGCN_OK;
   MGGCN_REQUIRE(C != nullptr, MGGCN_E_INVALID_ARG, "C is NULL");
   MGGCN_REQUIRE(K == 0 || (A && B), MGGCN_E_INVALID_ARG, "A / B is NULL");
-  const Shape s = plan_shape(pieces, opA, M, N, std::max<int64_t>(K, 1));
+  auto vec_width = [](const float* p, int64_t ld) {
+    if (aligned(p, 16) && ld % 4 == 0) return 4;
+    if (aligned(p, 8) && ld % 2 == 0) return 2;
+    return 1;
+  };
+  const int vecA = vec_width(A, lda), vecB = vec_width(B, ldb);
+  const bool rows16 = vecA == 4 && vecB == 4 && lda < kStreamMaxLd && ldb < kStreamMaxLd && ldc < kStreamMaxLd;
+  const Shape s = plan_shape(pieces, rows16, opA, M, N, std::max<int64_t>(K, 1));
   float* partial = nullptr;
   if (s.splits > 1) {
     const size_t need = mggcn_gemm_workspace_bytes(opA, opB, M, N, K);  // one size for both kernels
@@ -658,13 +994,7 @@ int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, con
                   ws_bytes, need);
     partial = static_cast<float*>(ws);
   }
-  auto vec_width = [](const float* p, int64_t ld) {
-    if (aligned(p, 16) && ld % 4 == 0) return 4;
-    if (aligned(p, 8) && ld % 2 == 0) return 2;
-    return 1;
-  };
-  GemmArgs g{opA, opB, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial, vec_width(A, lda), vec_width(B, ldb),
-             as_stream(stream)};
+  GemmArgs g{opA, opB, M, N, K, A, lda, B, ldb, C, ldc, beta, epilogue, partial, vecA, vecB, as_stream(stream)};
   hipStream_t st = g.st;
   const int rc = launch_all(g, s);
   if (rc) return rc;
@@ -685,8 +1015,9 @@ extern "C" {
 size_t mggcn_gemm_workspace_bytes(int opA, int opB, int64_t M, int64_t N, int64_t K) {
   (void)opB;
   if (M <= 0 || N <= 0 || K <= 0) return 0;
-  // enough for either kernel: they cut the inner dimension into different numbers of parts
-  const int splits = std::max(plan_shape(false, opA, M, N, K).splits, plan_shape(true, opA, M, N, K).splits);
+  // enough for every kernel: they cut the inner dimension into different numbers of parts
+  const int splits = std::max({plan_shape(false, false, opA, M, N, K).splits, plan_shape(false, true, opA, M, N, K).splits,
+                               plan_shape(true, false, opA, M, N, K).splits});
   if (splits <= 1) return 0;
   return align_up((size_t)splits * (size_t)M * (size_t)N * sizeof(float), kWsAlign);
 }
