@@ -307,6 +307,62 @@ __device__ inline void store_whole_tiles(const float16v (&acc)[TM][TN], int64_t 
   else sweep(std::integral_constant<int, 2>{});
 }
 
+// And for a wavefront at the edge of C: columns past N are masked once per 32-column tile, rows
+// past M fall outside the buffer descriptor (which ends with the last valid element) and are
+// dropped by its range check; the row part of the offset is then per lane (one addition per store).
+template <int TM, int TN>
+__device__ inline void store_edge_tiles(const float16v (&acc)[TM][TN], int64_t row0, int64_t col0, int64_t M,
+                                        int64_t N, int64_t split, float* __restrict__ C, int64_t ldc, float beta,
+                                        int epi, float* __restrict__ partial) {
+  if (row0 >= M || col0 >= N) return;
+  const int lane = threadIdx.x & 63;
+  const int frow = lane >> 5, fcol = lane & 31;
+  const bool to_partial = partial != nullptr;
+  float* out = to_partial ? partial + split * M * N : C;
+  const int64_t ldo = to_partial ? N : ldc;
+  const __amdgpu_buffer_rsrc_t rs =
+      buffer_over(out + row0 * ldo + col0, ((M - row0 - 1) * ldo + (N - col0)) * (int64_t)sizeof(float));
+  const uint32_t lane_off = (uint32_t)((4 * frow * ldo + fcol) * 4);
+  auto sweep = [&](auto mode) {
+    constexpr int kMode = decltype(mode)::value;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      if (col0 + j * 32 + fcol < N) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const uint32_t off = lane_off + (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4);
+            float v = acc[i][j][r];
+            if constexpr (kMode == 1) v = v > 0.f ? v : 0.f;
+            if constexpr (kMode == 2) {
+              const float old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
+              v = gemm_epilogue(v, old, beta, epi);
+            }
+            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, off, 0, 0);
+          }
+      }
+  };
+  if (to_partial || (beta == 0.f && epi == MGGCN_EPI_NONE)) sweep(std::integral_constant<int, 0>{});
+  else if (beta == 0.f && epi == MGGCN_EPI_RELU) sweep(std::integral_constant<int, 1>{});
+  else sweep(std::integral_constant<int, 2>{});
+}
+
+// per-lane byte offsets inside a wavefront's block of C stay below 2^31 for rows shorter than this
+constexpr int64_t kBufferMaxLd = (int64_t)1 << 21;
+
+// row0, col0 and everything else but the accumulators must be the same in all lanes.
+template <int TM, int TN>
+__device__ inline void write_tiles(const float16v (&acc)[TM][TN], int64_t row0, int64_t col0, int64_t M, int64_t N,
+                                   int64_t split, float* __restrict__ C, int64_t ldc, float beta, int epi,
+                                   float* __restrict__ partial) {
+  const int64_t ldo = partial ? N : ldc;
+  if (ldo >= kBufferMaxLd) store_tiles<TM, TN>(acc, row0, col0, false, M, N, split, C, ldc, beta, epi, partial);
+  else if (row0 + TM * 32 <= M && col0 + TN * 32 <= N)
+    store_whole_tiles<TM, TN>(acc, row0, col0, M, N, split, C, ldc, beta, epi, partial);
+  else store_edge_tiles<TM, TN>(acc, row0, col0, M, N, split, C, ldc, beta, epi, partial);
+}
+
 // WM x WN wavefronts tile the BM x BN block; each wavefront holds TM x TN accumulators of 32x32.
 // kFast: the host guarantees 16-byte aligned operands and whole tiles along N, so a block whose
 // M tile is whole loads its full k-steps with no checks at all (measured +15 %); the ragged last
@@ -333,7 +389,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
   __shared__ __attribute__((aligned(16))) float As[BK][LDA];
   __shared__ __attribute__((aligned(16))) float Bs[BK][LDB];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // a scalar
   const int wm = wave / WN, wn = wave % WN;
   int64_t tile_m, tile_n, split;
   if (!decode_tile(M - m_base, N, K, BM, BN, k_per_split, &tile_m, &tile_n, &split)) return;
@@ -395,7 +451,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma(int64_t m_base, int64_t M,
     __syncthreads();
   }
 
-  store_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, whole, M, N, split, C, ldc, beta, epi, partial);
+  write_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, M, N, split, C, ldc, beta, epi, partial);
 }
 
 
@@ -456,7 +512,7 @@ __device__ inline bool locate_tile(uint32_t id, uint32_t n_ids, uint32_t stride,
 }
 
 template <int BN, int WM, int WN, bool TA, bool TB>
-__global__ __launch_bounds__(kThreads) void gemm_stream(int64_t M, int64_t N, int64_t K,
+__global__ __launch_bounds__(kThreads, 2) void gemm_stream(int64_t M, int64_t N, int64_t K,
                                                          const float* __restrict__ A, int64_t lda,
                                                          const float* __restrict__ B, int64_t ldb,
                                                          float* __restrict__ C, int64_t ldc, float beta, int epi,
@@ -579,12 +635,7 @@ __global__ __launch_bounds__(kThreads) void gemm_stream(int64_t M, int64_t N, in
         locate_tile(cur.id + gridDim.x, n_ids, gridDim.x, tiles_m, tiles_n, splits, K, k_per_split, BM, BN, BK, &nxt);
     if (more) load_step(nxt, 0);
     multiply(stage);
-    if (cur.m0 + BM <= M)
-      store_whole_tiles<TM, TN>(acc, cur.m0 + wm * TM * 32, cur.n0 + wn * TN * 32, M, N, cur.split, C, ldc, beta, epi,
-                                partial);
-    else
-      store_tiles<TM, TN>(acc, cur.m0 + wm * TM * 32, cur.n0 + wn * TN * 32, false, M, N, cur.split, C, ldc, beta, epi,
-                          partial);
+    write_tiles<TM, TN>(acc, cur.m0 + wm * TM * 32, cur.n0 + wn * TN * 32, M, N, cur.split, C, ldc, beta, epi, partial);
     if (!more) break;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -730,7 +781,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_pieces(int64_t m_base, int64
   __shared__ __attribute__((aligned(16))) uint16_t As[3][BM][kPieceLd];
   __shared__ __attribute__((aligned(16))) uint16_t Bs[3][BN][kPieceLd];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // a scalar
   const int wm = wave / WN, wn = wave % WN;
   int64_t tile_m, tile_n, split;
   if (!decode_tile(M - m_base, N, K, BM, BN, k_per_split, &tile_m, &tile_n, &split)) return;
@@ -809,7 +860,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_pieces(int64_t m_base, int64
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] += fine[i][j][r];
-  store_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, whole, M, N, split, C, ldc, beta, epi, partial);
+  write_tiles<TM, TN>(acc, m0 + wm * TM * 32, n0 + wn * TN * 32, M, N, split, C, ldc, beta, epi, partial);
 }
 
 // Sum of the split-K partial products, in a fixed order: 8 lanes share one output element, each
@@ -926,7 +977,7 @@ int launch_all(const GemmArgs& g, const Shape& s) {
   if (s.pieces) {
     if (s.bn == 128) fast ? launch_pieces<128, true>(g, s, grid) : launch_pieces<128, false>(g, s, grid);
     else fast ? launch_pieces<64, true>(g, s, grid) : launch_pieces<64, false>(g, s, grid);
-  } else if (s.bk == 32 && fast && g.lda < kStreamMaxLd && g.ldb < kStreamMaxLd && g.ldc < kStreamMaxLd) {
+  } else if (s.bk == 32 && fast && g.lda < kStreamMaxLd && g.ldb < kStreamMaxLd) {
     // as many workgroups as the chip holds at once (a multiple of 8); each walks its share of the tiles
     const dim3 pgrid((unsigned)std::min<int64_t>(nblk, (s.wide ? 2 : 3) * 256), 1, 1);
 #define MGGCN_GEMM_LAUNCH(TA, TB)                                                                               \
@@ -984,7 +1035,7 @@ int gemm_run(bool pieces, int opA, int opB, int64_t M, int64_t N, int64_t K, con
     return 1;
   };
   const int vecA = vec_width(A, lda), vecB = vec_width(B, ldb);
-  const bool rows16 = vecA == 4 && vecB == 4 && lda < kStreamMaxLd && ldb < kStreamMaxLd && ldc < kStreamMaxLd;
+  const bool rows16 = vecA == 4 && vecB == 4 && lda < kStreamMaxLd && ldb < kStreamMaxLd;
   const Shape s = plan_shape(pieces, rows16, opA, M, N, std::max<int64_t>(K, 1));
   float* partial = nullptr;
   if (s.splits > 1) {
