@@ -130,8 +130,16 @@ def calibrate(mg, torch, dev, gib=8, reps=5):
     flop = mg.mggcn_probe_mfma(20000, sink)
     ms = timed(torch, lambda: mg.mggcn_probe_mfma(20000, sink), 3, warm=1)["min"]
     out["mfma_f32_registers_only_TFLOPs"] = round(flop / (ms * 1e-3) / 1e12, 1)
+    # the library's own GeMM on N(0,1) and on all-zero operands: the same instruction stream, and the chip runs it
+    # faster when the data do not switch (it lowers its clock under the load of LDS, load path and matrix pipes)
+    M, N, K = 2_449_029, 256, 256
+    A, B, C = buf[: M * K].view(M, K), buf[M * K: M * K + K * N].view(K, N), buf[n // 2: n // 2 + M * N].view(M, N)
+    for name, fill in (("normal", lambda t: t.normal_(generator=gen)), ("zero", lambda t: t.zero_())):
+        fill(A), fill(B)
+        ms = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, A, B, Cm=C), reps)["median"]
+        out[f"gemm_f32_{M}x{N}x{K}_{name}_operands_TFLOPs"] = round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
     log(f"calibration {out}")
-    del buf
+    del buf, A, B, C
     torch.cuda.empty_cache()
     return out
 
@@ -235,6 +243,18 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
         return {"mode": "profile-spmm", "config": "block", "calls": args.profile_spmm, "F": d_in, "nnz": nnz,
                 "no_reuse_bytes_fwd": spmm_bytes(nnz, nr, d_in), "no_reuse_bytes_bwd": spmm_bytes(nnz, nc, d_in),
                 "copy_bytes_each_way": 4 << 28}
+
+    if args.profile_gemm > 0:
+        step()
+        if args.zero_operands:  # the same launches on data that do not switch
+            for t_ in (P, W, G):
+                t_.zero_()
+        for k in (f"gemm_fwd_{d_in}x{d_out}", "gemm_wgrad", "gemm_hgrad"):
+            for _ in range(args.profile_gemm):
+                calls[k]()
+        torch.cuda.synchronize()
+        return {"mode": "profile-gemm", "config": "block", "calls": args.profile_gemm, "M": nr, "d_in": d_in, "d_out": d_out,
+                "operands": "zero" if args.zero_operands else "as in a step", "flop_per_call": 2 * nr * d_in * d_out}
 
     for _ in range(args.warmup):
         step()
@@ -604,7 +624,10 @@ def main() -> int:
                     help="with --profile-spmm: the feature width to run at (default: the epoch's widest SpMM)")
     ap.add_argument("--profile-gemm", type=int, default=0, metavar="N",
                     help="counter-collection mode: N calls of the first layer's forward GeMM (H W with the padded "
-                         "leading dimension the epoch uses) and N of its weight-gradient GeMM, then exit")
+                         "leading dimension the epoch uses) and N of its weight-gradient GeMM, then exit; block: N calls "
+                         "of each of the layer's three GeMMs")
+    ap.add_argument("--zero-operands", action="store_true",
+                    help="with --config block --profile-gemm: all-zero operands (the same launches on data that do not switch)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); "
