@@ -469,6 +469,57 @@ def test_gemm_tn_split_k(mg, dev, ref, M, N, K):
     assert np.array_equal(a, b), "split-K reduction must be reproducible"
 
 
+@pytest.mark.parametrize("M,N,K", [(70001, 128, 96), (40000, 192, 100), (300, 256, 64), (129, 384, 2052),
+                                   (128, 64, 68)])
+def test_gemm_aligned_operands_all_forms(mg, dev, ref, M, N, K):
+    """Rows that start on 16-byte boundaries take the kernel with buffer-addressed loads: 128 x 128 tiles for N a
+    multiple of 128, 128 x 64 otherwise; more tiles than resident workgroups (each walks several, and ids that only
+    pad the grid are skipped), a ragged last row tile, a ragged last k-step, all four operand forms, every epilogue."""
+    say(f"[gemm aligned] {M}x{N}x{K}")
+    A = wl.normal_f32(M + N, 31, (M, K))
+    Bm = wl.normal_f32(M + K, 32, (K, N))
+    want = ref.gemm(ref.OP_N, ref.OP_N, A.astype(np.float64), Bm.astype(np.float64))
+    Mp = (M + 3) // 4 * 4   # the transposed A needs rows of a multiple of four floats
+    At = np.zeros((K, Mp), dtype=np.float32)
+    At[:, :M] = A.T
+    Ad, Bd, Atd, Btd = to_dev(A, dev), to_dev(Bm, dev), to_dev(At, dev)[:, :M], to_dev(np.ascontiguousarray(Bm.T), dev)
+    plain = mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad, Bd).cpu().numpy()
+    assert_rows_close(plain, want, what="NN")
+    assert_rows_close(mg.mggcn_gemm(mg.OP_N, mg.OP_T, Ad, Btd).cpu().numpy(), want, what="NT")
+    assert_rows_close(mg.mggcn_gemm(mg.OP_T, mg.OP_N, Atd, Bd).cpu().numpy(), want, what="TN")
+    assert_rows_close(mg.mggcn_gemm(mg.OP_T, mg.OP_T, Atd, Btd).cpu().numpy(), want, what="TT")
+    C0 = wl.normal_f32(M, 33, (M, N))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad, Bd, epilogue=mg.EPI_RELU, Cm=Cd)
+    assert np.array_equal(Cd.cpu().numpy(), np.maximum(plain, 0))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad, Bd, epilogue=mg.EPI_RELU_MASK, Cm=Cd)
+    assert np.array_equal(Cd.cpu().numpy(), np.where(C0 > 0, plain, 0).astype(np.float32))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad, Bd, beta=1.0, Cm=Cd)
+    assert np.array_equal(Cd.cpu().numpy(), plain + C0)
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Ad, Bd, beta=1.0, epilogue=mg.EPI_RELU, Cm=Cd)
+    assert np.array_equal(Cd.cpu().numpy(), np.maximum(plain + C0, 0))
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 256, 50001), (256, 128, 33333), (100, 64, 40000)])
+def test_gemm_tn_split_k_aligned(mg, dev, ref, M, N, K):
+    """the weight gradient on aligned operands: split inner dimension whose last part ends in a ragged k-step"""
+    say(f"[gemm TN split-K aligned] {M}x{N}x{K}")
+    H = wl.normal_f32(K, 34, (K, M))
+    T = wl.normal_f32(K, 35, (K, N))
+    want = ref.gemm(ref.OP_T, ref.OP_N, H.astype(np.float64), T.astype(np.float64))
+    a = mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(H, dev), to_dev(T, dev)).cpu().numpy()
+    assert_rows_close(a, want, what="TN")
+    b = mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(H, dev), to_dev(T, dev)).cpu().numpy()
+    assert np.array_equal(a, b), "split-K reduction must be reproducible"
+    C0 = wl.normal_f32(M, 36, (M, N))
+    Cd = to_dev(C0, dev)
+    mg.mggcn_gemm(mg.OP_T, mg.OP_N, to_dev(H, dev), to_dev(T, dev), beta=1.0, Cm=Cd)
+    assert np.array_equal(Cd.cpu().numpy(), a + C0)
+
+
 def test_gemm_degenerate_shapes(mg, dev, ref):
     """empty outputs are no-ops; an empty inner dimension leaves epilogue(beta * C)"""
     import torch
