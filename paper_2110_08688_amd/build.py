@@ -41,7 +41,18 @@ def build(force: bool = False, jobs: int = 8) -> str:
     finally:
         os.environ.pop("MGGCN_FORCE_REBUILD", None)
     subprocess.check_call([HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs])
+    build_probes()
     return LIB
+
+
+def build_probes() -> list:
+    """Stand-alone measurement programs (probes/*.hip -> probes/<name>): not linked into the library."""
+    outs = []
+    for src in sorted(glob.glob(os.path.join(HERE, "probes", "*.hip"))):
+        exe = src[: -len(".hip")]
+        subprocess.check_call([HIPCC, *[f for f in FLAGS if f != "-fPIC"], "-o", exe, src])
+        outs.append(exe)
+    return outs
 
 
 if __name__ == "__main__":
