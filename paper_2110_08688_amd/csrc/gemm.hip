@@ -3,12 +3,15 @@
 //
 //   C = epilogue( op(A) op(B) + beta C )
 //
-// One kernel template.  A workgroup of 4 wavefronts owns a BM x BN tile of C and walks K in
-// steps of 32 (16 for a short inner dimension).  Both operand tiles are staged through LDS in k-major order (As[k][m], Bs[k][n])
-// whatever their layout in memory, because that is the order v_mfma_f32_32x32x2_f32 wants its
-// fragments in: lane l feeds A[m = l%32][k = l/32] and B[k = l/32][n = l%32], so a fragment is
-// 32 consecutive floats of one LDS row and is read without bank conflicts.  The next k-step's
-// global loads are issued before the MFMA loop of the current one.
+// Workgroups of 4 wavefronts own tiles of C and walk K in steps of 32 (16 for a short inner
+// dimension); operand tiles are staged through LDS.  v_mfma_f32_32x32x2_f32 wants lane l to feed
+// A[m = l%32][k = l/32] and B[k = l/32][n = l%32].
+//   gemm_stream  operands whose rows start on 16-byte boundaries (every large product of a GCN
+//                layer): buffer-addressed loads, two LDS stages, 128 x 128 tiles, several tiles
+//                per workgroup;
+//   gemm_mfma    everything else: 128 x 64 tiles, one LDS stage, checked loaders;
+//   gemm_pieces  the same product out of bfloat16 matrix instructions (an extension).
+// All three write C through the same epilogue (ReLU, ReLU' mask, beta = 1 fused).
 //
 // The shapes here are tall and skinny (M = vertex count, N and K a few hundred at most) except
 // for the weight gradient, whose inner dimension is the vertex count: that one is split along
