@@ -919,7 +919,9 @@ Shape plan_shape(bool pieces, bool aligned, int opA, int64_t M, int64_t N, int64
     // all workgroups resident at once: 256 CUs x 4, or x 2 for the kernels with 128 x 128 tiles and
     // their 60-67 KB of LDS (a few more would run as a second round behind the first and double
     // the kernel's time)
-    int64_t want = std::max<int64_t>((s.pieces || s.wide ? 512 : 1024) / tiles, 1);
+    // (gemm_stream with 128 x 64 tiles: 50-55 KB of LDS, three per CU)
+    const bool narrow_stream = !s.pieces && !s.wide && aligned && s.bk == 32 && N % kBN == 0;
+    int64_t want = std::max<int64_t>((s.pieces || s.wide ? 512 : narrow_stream ? 768 : 1024) / tiles, 1);
     want = std::min<int64_t>(want, ceil_div(K, 16 * BK));
     want = std::max<int64_t>(want, 1);
     s.k_per_split = (int64_t)align_up((size_t)ceil_div(K, want), BK);
