@@ -308,6 +308,11 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
         "gemm_tflops": round(3 * 2.0 * nr * d_in * d_out / (gemm_ms * 1e-3) / 1e12, 2),
         "gemm_mfma_utilisation": round(3 * 2.0 * nr * d_in * d_out / (gemm_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, 4),
         "ops_ms": {k: r4(v) for k, v in ops.items()},
+        # Under the paper's 1-D row distribution (broadcast stages, Section "partitioning") a GPU's backward product is
+        # its row block of A^^T times the whole gradient matrix: the same launch shape as the forward product (for the
+        # symmetric A^ the same block).  The transposed product timed here, over all 111 M columns of the block, is what
+        # the reduction-based alternative needs and the more expensive of the two.
+        "step_ms_with_a_forward_shaped_backward_product": round(2 * fwd_ms + gemm_ms, 4),
         "generate_s": round(gen_s, 3), "setup_s": setup,
         "box_calibration": calib,
         "roofline": roof, "roofline_transposed_launch": roof_b, "cpu_baseline": cpu,
