@@ -138,6 +138,9 @@ def calibrate(mg, torch, dev, gib=8, reps=5):
         fill(A), fill(B)
         ms = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, A, B, Cm=C), reps)["median"]
         out[f"gemm_f32_{M}x{N}x{K}_{name}_operands_TFLOPs"] = round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
+        if name == "normal":  # for scale: the vendor library's fp32 product behind torch.matmul, same operands
+            ms = timed(torch, lambda: torch.matmul(A, B, out=C), reps)["median"]
+            out[f"vendor_matmul_f32_{M}x{N}x{K}_TFLOPs"] = round(2.0 * M * N * K / (ms * 1e-3) / 1e12, 1)
     log(f"calibration {out}")
     del buf, A, B, C
     torch.cuda.empty_cache()
