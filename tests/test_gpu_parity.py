@@ -520,6 +520,26 @@ def test_gemm_tn_split_k_aligned(mg, dev, ref, M, N, K):
     assert np.array_equal(Cd.cpu().numpy(), a + C0)
 
 
+def test_gemm_very_long_rows_of_c(mg, dev, ref):
+    """Rows of C (and of A) 2^21 floats apart: offsets inside a wavefront's block of C no longer fit the 32-bit
+    lane offsets of the buffer stores, so the epilogue takes its 64-bit form and the operands the checked loaders."""
+    import torch
+
+    M, N, K, ld = 130, 64, 96, 1 << 21
+    say(f"[gemm long rows] {M}x{N}x{K} ld {ld}")
+    A = wl.normal_f32(5, 41, (M, K))
+    Bm = wl.normal_f32(5, 42, (K, N))
+    want = ref.gemm(ref.OP_N, ref.OP_N, A.astype(np.float64), Bm.astype(np.float64))
+    Abig = torch.zeros((M, ld), dtype=torch.float32, device=dev)
+    Abig[:, :K] = to_dev(A, dev)
+    Cbig = torch.full((M, ld), 7.0, dtype=torch.float32, device=dev)
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Abig[:, :K], to_dev(Bm, dev), Cm=Cbig[:, :N])
+    assert_rows_close(Cbig[:, :N].cpu().numpy(), want, what="long rows")
+    assert bool((Cbig[:, N:N + 64] == 7.0).all()) and bool((Cbig[:, -64:] == 7.0).all()), "padding columns must not be written"
+    mg.mggcn_gemm(mg.OP_N, mg.OP_N, Abig[:, :K], to_dev(Bm, dev), epilogue=mg.EPI_RELU, Cm=Cbig[:, :N])
+    assert_rows_close(Cbig[:, :N].cpu().numpy(), np.maximum(want, 0), pre=want, what="long rows, ReLU")
+
+
 def test_gemm_degenerate_shapes(mg, dev, ref):
     """empty outputs are no-ops; an empty inner dimension leaves epilogue(beta * C)"""
     import torch
