@@ -182,7 +182,7 @@ __device__ __forceinline__ void spmm_team_body(
       float r[VW];
 #pragma unroll
       for (int i = 0; i < VW; ++i) r[i] = apply_epilogue(acc[i], old[i], my_beta, my_epi);
-      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, r, 0.f, MGGCN_EPI_NONE, false);
+      store_out<VW>(Y + (int64_t)task.row * ldy + f0, nf, r, 0.f, MGGCN_EPI_NONE, false, (task.len_flags & kTaskLast) != 0);
     }
   }
 }
