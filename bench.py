@@ -472,17 +472,21 @@ def run_epoch_config(args, name, cfg, mg, wl, torch, dev, calib, brief=False):
         dst = torch.empty((n, ld), device=dev)
         epi = mg.EPI_RELU if (l + 1 < L and order == mg.ORDER_GEMM_FIRST) else mg.EPI_NONE
         ops[f"spmm_fwd_l{l}_F{F}"] = timed(torch, lambda: mg.mggcn_spmm(graph, mg.OP_N, src[:, :F], epilogue=epi, Y=dst[:, :F]), reps)
+        # backward: the ReLU' mask of the layer below rides on whichever product writes H_G (in place over the activation)
+        bepi = mg.EPI_RELU_MASK if (l > 0 and order == mg.ORDER_SPMM_FIRST) else mg.EPI_NONE
         if l > 0 or order == mg.ORDER_GEMM_FIRST:
-            ops[f"spmm_bwd_l{l}_F{F}"] = timed(torch, lambda: mg.mggcn_spmm(graph, mg.OP_T, src[:, :F], Y=dst[:, :F]), reps)
+            ops[f"spmm_bwd_l{l}_F{F}"] = timed(torch, lambda: mg.mggcn_spmm(graph, mg.OP_T, src[:, :F], epilogue=bepi, Y=dst[:, :F]), reps)
         H = X if l == 0 else torch.randn((n, (dims[l] + 15) // 16 * 16), device=dev)[:, :dims[l]]
         out = torch.empty((n, (dims[l + 1] + 15) // 16 * 16), device=dev)[:, :dims[l + 1]]
         wg = torch.empty_like(Ws[l])
-        hg = torch.empty((n, (dims[l] + 15) // 16 * 16), device=dev)[:, :dims[l]] if l > 0 else None
+        hg = torch.randn((n, (dims[l] + 15) // 16 * 16), device=dev)[:, :dims[l]] if l > 0 else None
         ws = mg.gemm_workspace(mg.OP_T, mg.OP_N, dims[l], dims[l + 1], n, dev)
-        ops[f"gemm_fwd_l{l}_{dims[l]}x{dims[l + 1]}"] = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, H, Ws[l], Cm=out), reps)
+        fepi = mg.EPI_RELU if (l + 1 < L and order == mg.ORDER_SPMM_FIRST) else mg.EPI_NONE
+        ops[f"gemm_fwd_l{l}_{dims[l]}x{dims[l + 1]}"] = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_N, H, Ws[l], epilogue=fepi, Cm=out), reps)
         ops[f"gemm_wgrad_l{l}"] = timed(torch, lambda: mg.mggcn_gemm(mg.OP_T, mg.OP_N, H, out, Cm=wg, ws=ws), reps)
         if l > 0:
-            ops[f"gemm_hgrad_l{l}"] = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_T, out, Ws[l], Cm=hg), reps)
+            hepi = mg.EPI_RELU_MASK if order == mg.ORDER_GEMM_FIRST else mg.EPI_NONE
+            ops[f"gemm_hgrad_l{l}"] = timed(torch, lambda: mg.mggcn_gemm(mg.OP_N, mg.OP_T, out, Ws[l], epilogue=hepi, Cm=hg), reps)
         del src, dst
     logits = torch.randn((n, (dims[L] + 15) // 16 * 16), device=dev)[:, :dims[L]]
     ops["softmax_ce"] = timed(torch, lambda: mg.mggcn_softmax_ce(logits, labels), reps)

@@ -289,21 +289,29 @@ __device__ inline void store_whole_tiles(const float16v (&acc)[TM][TN], int64_t 
   // the choice is the same for every element: made once, outside the unrolled stores
   auto sweep = [&](auto mode) {
     constexpr int kMode = decltype(mode)::value;  // 0: as it is, 1: ReLU, 2: needs the old value of C
+    // the old values of one 32 x 32 tile are all requested before the first of them is used: one
+    // memory latency per tile instead of one per element (loads and stores through one descriptor
+    // are not reordered by the compiler)
+    float old[kMode == 2 ? 16 : 1];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (kMode == 2) {
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            old[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                rs, lane_off, (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4), 0));
+        }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const uint32_t reg_off = (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4);
           float v = acc[i][j][r];
           if constexpr (kMode == 1) v = v > 0.f ? v : 0.f;
-          if constexpr (kMode == 2) {
-            const float old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane_off, reg_off, 0));
-            v = gemm_epilogue(v, old, beta, epi);
-          }
+          if constexpr (kMode == 2) v = gemm_epilogue(v, old[r], beta, epi);
           __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, lane_off, reg_off, 0);
         }
+      }
   };
   if (to_partial || (beta == 0.f && epi == MGGCN_EPI_NONE)) sweep(std::integral_constant<int, 0>{});
   else if (beta == 0.f && epi == MGGCN_EPI_RELU) sweep(std::integral_constant<int, 1>{});
@@ -328,22 +336,27 @@ __device__ inline void store_edge_tiles(const float16v (&acc)[TM][TN], int64_t r
   const uint32_t lane_off = (uint32_t)((4 * frow * ldo + fcol) * 4);
   auto sweep = [&](auto mode) {
     constexpr int kMode = decltype(mode)::value;
+    float old[kMode == 2 ? 16 : 1];  // requested together, as above
 #pragma unroll
     for (int j = 0; j < TN; ++j)
       if (col0 + j * 32 + fcol < N) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i) {
+          if constexpr (kMode == 2) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              old[r] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                  rs, lane_off + (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4), 0, 0));
+          }
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const uint32_t off = lane_off + (uint32_t)(((i * 32 + 8 * (r / 4) + (r % 4)) * ldo + j * 32) * 4);
             float v = acc[i][j][r];
             if constexpr (kMode == 1) v = v > 0.f ? v : 0.f;
-            if constexpr (kMode == 2) {
-              const float old = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0));
-              v = gemm_epilogue(v, old, beta, epi);
-            }
+            if constexpr (kMode == 2) v = gemm_epilogue(v, old[r], beta, epi);
             __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v), rs, off, 0, 0);
           }
+        }
       }
   };
   if (to_partial || (beta == 0.f && epi == MGGCN_EPI_NONE)) sweep(std::integral_constant<int, 0>{});
