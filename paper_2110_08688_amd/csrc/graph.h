@@ -40,6 +40,8 @@ struct TaskSet {
   std::vector<int64_t> task_begin;  // n_panels + 1 offsets into the task list (panel-major; inside a panel longest first)
   std::vector<int64_t> fix_begin;   // n_panels + 1 offsets into the fix-up records
   std::vector<std::array<int64_t, kLenClasses>> cnt_ge;  // per panel: tasks of length >= 8 << i
+  std::vector<int64_t> cnt_nonempty;  // per panel: tasks with at least one entry (the rest, all of them rows
+                                      // without any entry, are the tail of the panel's task list, rows ascending)
   int64_t n_slots = 0;              // partial-sum rows needed by the widest panel
   Task* d_tasks = nullptr;
   FixRow* d_fix = nullptr;

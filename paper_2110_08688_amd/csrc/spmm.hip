@@ -207,6 +207,70 @@ __global__ __launch_bounds__(kThreads) void spmm_fixup(const FixRow* __restrict_
   }
 }
 
+// Rows of op(A^) without a single entry, beta = 0: their result is zero whatever the epilogue, and
+// their tasks are the tail of a pass's task list (zero length sorts last; rows ascending).  They
+// are written here at the rate of a fill instead of each taking a lane team of the gather kernel
+// through its whole prologue: 79 M such rows of 128 floats took 10.9 ms there, a plain fill of the
+// same memory 6.2 ms (the transposed product of a 13.9 M x 111 M row block has that many).
+// One lane per VW floats of a row, `lanes` (a power of two, at most 64) per row; a wavefront takes up to
+// 64 consecutive tasks, reads each task once (one lane each) and hands the row numbers round by shuffles.
+template <int VW>
+__global__ __launch_bounds__(kThreads) void spmm_zero_rows(const Task* __restrict__ tasks, int64_t n, int F, int lanes_log2,
+                                                            int rows_per_team, float* __restrict__ Y, int64_t ldy,
+                                                            float* __restrict__ partial, int64_t ldp) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int tpw = 64 >> lanes_log2;  // teams (rows side by side) per wavefront
+  const int team = lane >> lanes_log2, fl = lane & ((1 << lanes_log2) - 1);
+  const int per_wave = tpw * rows_per_team;  // <= 64
+  const int64_t base = ((int64_t)blockIdx.x * (kThreads / 64) + wave) * per_wave;
+  int32_t my_row = 0, my_slot = -1;
+  if (lane < per_wave && base + lane < n) {
+    my_row = tasks[base + lane].row;
+    my_slot = tasks[base + lane].slot;
+  }
+  const int f0 = fl * VW;
+  const int nf = min(VW, F - f0);
+  const float zero[VW] = {};
+  for (int j = 0; j < rows_per_team; ++j) {
+    const int r = j * tpw + team;  // the same for all lanes of a team; every lane takes part in the shuffles
+    const int32_t row = __shfl(my_row, r), slot = __shfl(my_slot, r);
+    if (base + r < n && nf > 0) {
+      // a zero-length piece of a cut row (its sum lives in the partial table) is zero there
+      float* dst = slot < 0 ? Y + (int64_t)row * ldy + f0 : partial + (int64_t)slot * ldp + f0;
+      store_out<VW>(dst, nf, zero, 0.f, MGGCN_EPI_NONE, false, slot < 0);
+    }
+  }
+}
+
+// false: the shape does not fit the fill kernel (the rows stay with the gather launch)
+bool zero_rows_shape(const float* Y, int64_t ldy, int F, int* vw, int* lanes_log2, int* rows_per_team) {
+  *vw = 1;
+  if (aligned(Y, 16) && ldy % 4 == 0) *vw = 4;
+  else if (aligned(Y, 8) && ldy % 2 == 0) *vw = 2;
+  *lanes_log2 = 0;
+  while ((1 << *lanes_log2) * *vw < F && *lanes_log2 < 6) ++*lanes_log2;
+  if ((int64_t)(1 << *lanes_log2) * *vw < F) return false;
+  *rows_per_team = std::min(8, 64 / (64 >> *lanes_log2));
+  return true;
+}
+
+int launch_zero_rows(const Task* tasks, int64_t n, int F, float* Y, int64_t ldy, float* partial, int64_t ldp, hipStream_t s) {
+  int vw, lanes_log2, rows_per_team;
+  MGGCN_REQUIRE(zero_rows_shape(Y, ldy, F, &vw, &lanes_log2, &rows_per_team), MGGCN_E_OVERFLOW,
+                "F = %d too wide for the zero-row kernel", F);
+  const int64_t rows_per_block = (int64_t)(kThreads / 64) * (64 >> lanes_log2) * rows_per_team;
+  const int64_t blocks = ceil_div(n, rows_per_block);
+  MGGCN_REQUIRE(blocks < ((int64_t)1 << 31), MGGCN_E_OVERFLOW, "zero-row grid too large");
+#define MGGCN_ZERO_ROWS(VW) \
+  spmm_zero_rows<VW><<<(unsigned)blocks, kThreads, 0, s>>>(tasks, n, F, lanes_log2, rows_per_team, Y, ldy, partial, ldp)
+  if (vw == 4) MGGCN_ZERO_ROWS(4);
+  else if (vw == 2) MGGCN_ZERO_ROWS(2);
+  else MGGCN_ZERO_ROWS(1);
+#undef MGGCN_ZERO_ROWS
+  MGGCN_LAUNCH_CHECK();
+  return MGGCN_OK;
+}
+
 int launch_any_f32(int vw, int lpr, const LaunchArgs& a) {
   switch (vw) {
     case 4: return launch_lpr<float, 4>(lpr, a);
@@ -433,6 +497,8 @@ int spmm_check_args(const mggcn_graph* g, int op, const void* X, int64_t ldx, in
 
 namespace {
 
+constexpr int64_t kZeroRowsWorthALaunch = 1 << 16;  // fewer rows without entries stay in the gather launch
+
 // One product over the first F columns of X / Y with the given task tables.
 int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts, const void* X, int64_t ldx,
                    int vw, int32_t F, float beta, int epilogue, float* Y, int64_t ldy, void* stream,
@@ -451,7 +517,14 @@ int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts
   while ((1 << (top + 1)) <= gpt_max) ++top;  // gpt_max = 1 << top
   for (int32_t p = 0; p < ts.n_panels; ++p) {
     // bins of tasks by length; tasks are sorted longest first, so every bin is a contiguous range
-    const int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
+    int64_t ntasks = ts.task_begin[(size_t)p + 1] - ts.task_begin[p];
+    // beta = 0: rows without entries become zeros; many of them go to the fill kernel below
+    int64_t n_zero = (beta == 0.f) ? ntasks - ts.cnt_nonempty[(size_t)p] : 0;
+    {
+      int zvw, zlanes, zrows;
+      if (n_zero < kZeroRowsWorthALaunch || !zero_rows_shape(Y, ldy, F, &zvw, &zlanes, &zrows)) n_zero = 0;
+    }
+    ntasks -= n_zero;
     BinTable& bt = a.bins;
     bt.n_bins = 0;
     bt.block_begin[0] = 0;
@@ -470,6 +543,10 @@ int spmm_run_slice(const mggcn_graph* g, const Orientation& o, const TaskSet& ts
     a.tasks = ts.d_tasks + ts.task_begin[p];
     if (bt.n_bins > 0) {
       const int rc = launch(vw, lpr, a);
+      if (rc) return rc;
+    }
+    if (n_zero > 0) {
+      const int rc = launch_zero_rows(a.tasks + ntasks, n_zero, F, Y, ldy, g->d_partial, g->ldp, a.stream);
       if (rc) return rc;
     }
     const int64_t nfix = ts.fix_begin[(size_t)p + 1] - ts.fix_begin[p];

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void fill_fix(int64_t n_rows, int P, int 
 
 // out[p * kSummary + ...]: first task, first fix-up record, slots of panel p, then for k = 0..6 the number of its
 // tasks at least 8 << k long (keys ascend: longest first); entry P holds the totals.
-constexpr int kSummary = 3 + kLenClasses;
+constexpr int kSummary = 3 + kLenClasses + 1;  // the last one: tasks with at least one entry
 __global__ void summarise(int64_t n_rows, int P, int seg_len, const int64_t* __restrict__ task_off,
                           const int64_t* __restrict__ fix_off, const int64_t* __restrict__ slot_off,
                           const uint32_t* __restrict__ sorted_keys, int64_t* __restrict__ out) {
@@ -175,7 +175,7 @@ __global__ void summarise(int64_t n_rows, int P, int seg_len, const int64_t* __r
   if (k == 1) out[p * kSummary + 1] = fix_off[q0];
   if (k == 2) out[p * kSummary + 2] = p < P ? slot_off[q0 + n_rows] - slot_off[q0] : 0;
   if (k >= 3 && p < P) {
-    const int32_t len = 8 << (k - 3);
+    const int32_t len = k < 3 + kLenClasses ? 8 << (k - 3) : 1;
     int64_t n = 0;
     if (len <= seg_len) {  // tasks of panel p with key <= p * (seg_len + 1) + (seg_len - len)
       const uint32_t bound = (uint32_t)p * (uint32_t)(seg_len + 1) + (uint32_t)(seg_len - len);
@@ -238,6 +238,7 @@ int build_task_set_device(TaskSet* ts, int64_t n_rows, const IT* rowptr, const u
   ts->task_begin.assign((size_t)P + 1, 0);
   ts->fix_begin.assign((size_t)P + 1, 0);
   ts->cnt_ge.assign((size_t)P, {});
+  ts->cnt_nonempty.assign((size_t)P, 0);
   ts->n_slots = 0;
   ts->d_tasks = d_tasks;
   ts->d_fix = d_fix;
@@ -290,6 +291,7 @@ int build_task_set_device(TaskSet* ts, int64_t n_rows, const IT* rowptr, const u
     if (p < P) {
       ts->n_slots = std::max(ts->n_slots, sum[(size_t)p * kSummary + 2]);
       for (int k = 0; k < kLenClasses; ++k) ts->cnt_ge[(size_t)p][(size_t)k] = sum[(size_t)p * kSummary + 3 + k];
+      ts->cnt_nonempty[(size_t)p] = sum[(size_t)p * kSummary + 3 + kLenClasses];
     }
   }
   return MGGCN_OK;

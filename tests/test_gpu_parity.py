@@ -437,6 +437,51 @@ def test_spmm_column_panels(mg, dev, ref, spmm_graphs, name, P, seg):
         assert_rows_close(masked, np.where(Y0 > 0, want, 0.0), what=f"panels mask F={F}")
 
 
+def test_spmm_many_rows_without_entries(mg, dev, ref):
+    """The transposed product of a row block with far more columns than entries: most of its output rows hold no
+    entry.  With beta = 0 they are written by the fill kernel (zeros whatever the epilogue), with beta = 1 they
+    stay; widths with 16-, 8- and 4-byte lanes, a padded and an unaligned output, panels."""
+    import torch
+
+    g = wl.row_block(3000, 400_000, 60_000, 2.5, 300.0, 1.6, 11)
+    say(f"[spmm rows without entries] {g.n_rows} x {g.n_cols}, {g.nnz} entries")
+    rng = np.random.default_rng(12)
+    dr = rng.integers(1, 500, g.n_rows).astype(np.int32)
+    dc = rng.integers(1, 500, g.n_cols).astype(np.int32)
+    rp, ci, val = ref.csr_normalize(g.n_rows, g.n_cols, g.rowptr, g.colidx, deg_row=dr, deg_col=dc)
+    v32 = val.astype(np.float32)
+    d = [to_dev(a, dev) for a in (rp, ci, v32)]
+    t = mg.mggcn_csr_transpose(g.n_rows, g.n_cols, *d)
+    empty = np.diff(t[0].cpu().numpy()) == 0
+    assert empty.sum() > 300_000, "the case must hold enough rows without entries for the fill kernel to be chosen"
+    for panels in (0, 4):
+        G = mg.Graph(g.n_rows, g.n_cols, *d, transpose=t, F_max=128, n_panels=panels)
+        for F, ld, shift in ((128, 128, 0), (41, 48, 0), (41, 41, 0), (6, 8, 0), (33, 36, 1)):
+            U = wl.normal_f32(20 + F, 1, (g.n_rows, F))
+            want = ref.spmm(ref.OP_T, g.n_rows, g.n_cols, rp, ci, v32.astype(np.float64), U.astype(np.float64))
+            Y0 = wl.normal_f32(20 + F, 2, (g.n_cols, ld))
+            flat = torch.full((g.n_cols * ld + shift,), 5.0, dtype=torch.float32, device=dev)
+            Yd = flat[shift:].view(g.n_cols, ld)  # shift = 1: rows start on odd 4-byte boundaries
+            for beta, epi in ((0.0, mg.EPI_NONE), (0.0, mg.EPI_RELU), (0.0, mg.EPI_RELU_MASK), (1.0, mg.EPI_NONE)):
+                Yd.copy_(to_dev(Y0, dev))
+                mg.mggcn_spmm(G, mg.OP_T, to_dev(U, dev), beta=beta, epilogue=epi, Y=Yd[:, :F])
+                got = Yd.cpu().numpy()
+                exp = want + (Y0[:, :F].astype(np.float64) if beta else 0.0)
+                if epi == mg.EPI_RELU:
+                    exp = np.maximum(exp, 0.0)
+                if epi == mg.EPI_RELU_MASK:
+                    exp = np.where(Y0[:, :F] > 0, exp, 0.0)
+                assert_rows_close(got[:, :F], exp, pre=want if epi != mg.EPI_NONE else None,
+                                  what=f"P={panels} F={F} ld={ld} beta={beta} epi={epi}")
+                if beta == 0.0:
+                    assert not got[empty][:, :F].any(), "rows without entries must be exactly zero"
+                else:
+                    assert np.array_equal(got[empty][:, :F], Y0[empty][:, :F]), "beta = 1 leaves rows without entries as they are"
+                assert np.array_equal(got[:, F:], Y0[:, F:]), "padding columns must not be written"
+            if shift:
+                assert float(flat[0]) == 5.0
+
+
 # ----------------------------------------------------------------------------------------------
 # a1 / a7 / a8: GeMM
 # ----------------------------------------------------------------------------------------------
