@@ -40,7 +40,7 @@ FP32_MFMA_PEAK_TFLOPS = 157.3
 # counters sit between L2 and the fabric: fills served by the 256 MB Infinity Cache are included, so
 # the figure is an upper bound of the HBM traffic.
 MEASURED_TRAFFIC = {
-    "block": {"profile": "profiles/spmm_block_F128_pmc.md", "spmm_fwd": 97_277_283_043, "spmm_bwd": 165_753_170_417},
+    "block": {"profile": "profiles/spmm_block_F128_pmc.md", "spmm_fwd": 97_286_051_699, "spmm_bwd": 164_695_447_106},
     "large": {"profile": "profiles/spmm_large_pmc.md", "spmm_fwd_F256": 129_270_000_000, "spmm_fwd_F100": 63_700_000_000,
               "spmm_fwd_F47": 31_500_000_000},
     "medium": {"profile": "profiles/spmm_medium_F128_pmc.md", "spmm_fwd_F128": 17_018_680_064},
@@ -284,7 +284,8 @@ def run_block(args, cfg, mg, wl, torch, dev, calib):
     lanes = min(64, 1 << max(0, (d_in + 3) // 4 - 1).bit_length())
     roof = roofline_object(f"spmm_tasks<float,VW=4,LPR={lanes},U=4>: forward product A^ X at F={d_in}, one launch per call",
                            fwd_ms, tr_f, eff_f, min_f, flops, calib, mt["profile"], graph.panels(d_in))
-    roof_b = roofline_object(f"spmm_tasks<float,VW=4,LPR={lanes},U=4>: transposed product A^^T U at F={d_in} ({nc} output rows)",
+    roof_b = roofline_object(f"spmm_tasks<float,VW=4,LPR={lanes},U=4> + spmm_zero_rows<4>: transposed product A^^T U at F={d_in} ({nc} output rows: "
+                             f"the gather launch over the rows that hold entries, the fill launch over the others, the small fix-up launch)",
                              bwd_ms, tr_b, eff_b, min_b, flops, calib, mt["profile"], graph.panels(d_in, mg.OP_T))
 
     cpu = None
