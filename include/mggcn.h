@@ -254,6 +254,9 @@ int mggcn_f32_to_bf16(int64_t rows, int32_t cols, const float* src /*dev*/, int6
  * beta is 0 or 1.  fp32 inputs, fp32 MFMA accumulation.  opA = T with a long inner dimension
  * (the weight gradient W_G = H^T HW_G of Eq. 10, inner size = vertex count) is split along K
  * into partial products held in ws and summed in a fixed order.
+ * Any alignment and leading dimension is accepted; operands whose rows start on 16-byte boundaries
+ * (A and B 16-byte aligned, lda and ldb multiples of 4) with N a multiple of 64 and K >= 64 take the
+ * faster of the two kernels (about 1.1x; results agree to rounding, the order of summation differs).
  * Workspace: mggcn_gemm_workspace_bytes (0 for opA = N; one size serves mggcn_gemm and
  * mggcn_gemm_bf16x3).
  * ---------------------------------------------------------------------------------------- */
